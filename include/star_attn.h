@@ -1,0 +1,152 @@
+/*
+ * star_attn.h -- C ABI of the Star Attention hot path on one MI355X (gfx950).
+ *
+ * Star Attention (arXiv 2411.17116) runs long-context inference in two phases.
+ * Phase 1 (Section 2.1, Algorithm 1, Figure 2) encodes the context with
+ * block-local causal attention in which every block after the first is
+ * prefixed by an anchor (the start of the first block); only the non-anchor
+ * K/V is kept.  Phase 2 (Section 2.2, Eq. 1-4, Algorithm 2) lets query and
+ * generated tokens attend to the whole cache: each cached part yields a local
+ * attention output and the log of its softmax denominator, and the parts are
+ * merged by rescaling with those log-sum-exp statistics.  The paper's context
+ * hosts are context blocks resident on the one GPU.
+ *
+ * Conventions
+ *   - Every pointer is DEVICE memory owned by the caller unless it says "host".
+ *     The library never allocates, frees or keeps a pointer after a call
+ *     returns, and holds no state between calls.
+ *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and the function returns
+ *     without synchronising.  Calls on one stream run in order.
+ *   - All tensors are contiguous, row-major, last index fastest.
+ *   - dtype: STAR_ATTN_F32 (fp32 storage and arithmetic) or STAR_ATTN_BF16
+ *     (bf16 storage, bf16 MFMA with fp32 accumulation and fp32 softmax).
+ *     Partial outputs, LSE values and the workspace are always fp32.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - All validation happens on the host before anything is enqueued; a
+ *     non-zero return means no work was enqueued and no buffer was touched.
+ *   - Results are deterministic (no floating-point atomics).
+ */
+#ifndef STAR_ATTN_H
+#define STAR_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  STAR_ATTN_F32 = 0,
+  STAR_ATTN_BF16 = 1
+};
+
+/* Status codes: 0 = success, negative = error (nothing was enqueued). */
+enum {
+  STAR_ATTN_OK = 0,
+  STAR_ATTN_ERR_INVALID_SHAPE = -1,        /* non-positive size, Hq % Hkv != 0, bad q_len/cache_len */
+  STAR_ATTN_ERR_NULL_POINTER = -2,         /* a required pointer is NULL */
+  STAR_ATTN_ERR_UNSUPPORTED_HEAD_DIM = -3, /* fp32: 64 or 128; bf16: 128 */
+  STAR_ATTN_ERR_UNSUPPORTED_DTYPE = -4,
+  STAR_ATTN_ERR_ANCHOR_GT_BLOCK = -5,      /* anchor outside [0, block] */
+  STAR_ATTN_ERR_CACHE_OVERFLOW = -6,       /* ctx_len or cache_len + q_len exceeds cache_capacity */
+  STAR_ATTN_ERR_WORKSPACE_TOO_SMALL = -7,
+  STAR_ATTN_ERR_LAUNCH_FAILED = -8,        /* the HIP runtime refused a launch */
+  STAR_ATTN_ERR_MISALIGNED = -9            /* a tensor pointer is not 16-byte aligned */
+};
+
+/* Problem shape; sizes in elements / tokens. */
+typedef struct star_attn_shape {
+  int32_t dtype;          /* STAR_ATTN_F32 or STAR_ATTN_BF16 */
+  int32_t batch;          /* B  */
+  int32_t n_q_heads;      /* Hq */
+  int32_t n_kv_heads;     /* Hkv, divides Hq */
+  int32_t head_dim;       /* d  */
+  int32_t reserved;       /* set to 0 */
+  int64_t ctx_len;        /* L: context tokens */
+  int64_t block;          /* b >= 1: block size; n = ceil(L / b) blocks, the last may be short */
+  int64_t anchor;         /* a in [0, b]: the first a context tokens prefix every block but the first */
+  int64_t cache_capacity; /* rows per (batch, KV head) in the caches: >= L + every later append */
+  float   softmax_scale;  /* 0 selects 1/sqrt(d) (Eq. 1) */
+  float   reserved2;      /* set to 0 */
+} star_attn_shape;
+
+/*
+ * Bytes of device workspace star_attn_phase2 needs for calls with
+ * q_len <= max_q_len (split-KV partial outputs and their log-sum-exps).
+ * star_attn_phase1 needs none.  Returns 0 for an invalid shape.
+ */
+size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len);
+
+/*
+ * Phase 1: context encoding (Section 2.1; Algorithm 1; Figure 2).
+ *
+ * Context row p in block i = p / b (0-based) attends causally to
+ *   keys [0, p]                      if i == 0,
+ *   keys [0, a) and [i*b, p]         otherwise,
+ * with logits scale * q.k and a softmax over exactly those keys.  Rows of the
+ * anchor copies are not outputs and their K/V is never stored: the caches get
+ * every context token exactly once.
+ *
+ *   Q        in   [B, L, Hq,  d]
+ *   K, V     in   [B, L, Hkv, d]   (taken as post-RoPE; the anchor keeps its
+ *                                   original positions, so one K serves both roles)
+ *   O_ctx    out  [B, L, Hq, d]    same dtype as the inputs
+ *   LSE_ctx  out  [B, Hq, L] fp32, natural log of each row's softmax
+ *                 denominator of the scaled logits; may be NULL
+ *   K_cache, V_cache  out  [B, Hkv, cache_capacity, d]; rows [0, L) are written,
+ *                 the rest is left untouched
+ *   workspace     unused by this call (may be NULL / 0)
+ */
+int star_attn_phase1(const star_attn_shape* shape,
+                     const void* Q, const void* K, const void* V,
+                     void* O_ctx, float* LSE_ctx,
+                     void* K_cache, void* V_cache,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Phase 2: query encoding or one decode step (Section 2.2; Eq. 1-4; Algorithm 2).
+ *
+ * The q_len new tokens' K/V are first appended at cache rows
+ * [cache_len, cache_len + q_len); then new token j attends to cache rows
+ * [0, cache_len + j] (all context keys, the earlier tail tokens, and itself).
+ * The cache is processed as parts: part m < n is context block m
+ * (rows [m*b, min((m+1)*b, L))), part n is the tail (rows [L, cache_len + j]).
+ * Each part gives A_m (Eq. 1) and lse_m = log of Eq. 2; the result is
+ * O = sum_m exp(lse_m - lse) A_m with lse = log sum_m exp(lse_m)  (Eq. 3-4).
+ * Parts may be split further internally; what is exposed is per part.
+ *
+ *   cache_len  tokens already cached: L for the query call, then L + lq, ...
+ *              (the caller advances it by q_len after each call); >= L
+ *   Qq         in   [B, q_len, Hq,  d]
+ *   Kq, Vq     in   [B, q_len, Hkv, d]
+ *   K_cache, V_cache  in/out, layout as in phase 1
+ *   O_part     out  [B, P, Hq, q_len, d] fp32, P = n + 1; may be NULL
+ *   LSE_part   out  [B, P, Hq, q_len]    fp32 (-inf for an empty part); may be
+ *              NULL; O_part and LSE_part must be both given or both NULL
+ *   O          out  [B, q_len, Hq, d], dtype of the inputs
+ *   workspace  at least star_attn_workspace_bytes(shape, q_len) bytes, 256-byte
+ *              aligned; contents are scratch
+ */
+int star_attn_phase2(const star_attn_shape* shape,
+                     int64_t cache_len, int64_t q_len,
+                     const void* Qq, const void* Kq, const void* Vq,
+                     void* K_cache, void* V_cache,
+                     float* O_part, float* LSE_part,
+                     void* O,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static, NUL-terminated description of a status code (host memory, never freed). */
+const char* star_attn_status_string(int status);
+
+/*
+ * Name of the kernel path a shape would use ("f32-valu", "bf16-mfma"), for
+ * logs and benchmarks; NULL for an unsupported shape.  Host memory, static.
+ */
+const char* star_attn_kernel_path(const star_attn_shape* shape);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STAR_ATTN_H */

@@ -1,0 +1,142 @@
+"""ctypes binding of libstarattn.so (see include/star_attn.h for the contract)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+F32 = 0
+BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class StarAttnError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"star_attn: {what} (status {code})")
+        self.code = code
+
+
+class StarShape(ctypes.Structure):
+    """Mirror of `star_attn_shape`."""
+    _fields_ = [
+        ("dtype", ctypes.c_int32), ("batch", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("ctx_len", ctypes.c_int64), ("block", ctypes.c_int64), ("anchor", ctypes.c_int64),
+        ("cache_capacity", ctypes.c_int64),
+        ("softmax_scale", ctypes.c_float), ("reserved2", ctypes.c_float),
+    ]
+
+    @classmethod
+    def make(cls, dtype, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, block, anchor,
+             cache_capacity, softmax_scale=0.0) -> "StarShape":
+        if isinstance(dtype, torch.dtype):
+            dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(dtype, -1)
+        elif isinstance(dtype, str):
+            dtype = {"fp32": F32, "bf16": BF16}.get(dtype, -1)
+        return cls(int(dtype), int(batch), int(n_q_heads), int(n_kv_heads), int(head_dim), 0,
+                   int(ctx_len), int(block), int(anchor), int(cache_capacity),
+                   float(softmax_scale), 0.0)
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libstarattn.so")
+
+
+def load_library():
+    """Load the built library; raises if it has not been built (no fallback)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it with `python -m paper_2411_17116_amd.build`")
+    lib = ctypes.CDLL(path)
+    P = ctypes.POINTER(StarShape)
+    vp, sz, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64
+    lib.star_attn_workspace_bytes.restype = sz
+    lib.star_attn_workspace_bytes.argtypes = [P, i64]
+    lib.star_attn_phase1.restype = ctypes.c_int
+    lib.star_attn_phase1.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.star_attn_phase2.restype = ctypes.c_int
+    lib.star_attn_phase2.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.star_attn_status_string.restype = ctypes.c_char_p
+    lib.star_attn_status_string.argtypes = [ctypes.c_int]
+    lib.star_attn_kernel_path.restype = ctypes.c_char_p
+    lib.star_attn_kernel_path.argtypes = [P]
+    _LIB = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().star_attn_status_string(int(code)).decode()
+
+
+def kernel_path(shape: StarShape) -> Optional[str]:
+    r = load_library().star_attn_kernel_path(ctypes.byref(shape))
+    return r.decode() if r else None
+
+
+def workspace_bytes(shape: StarShape, max_q_len: int) -> int:
+    return int(load_library().star_attn_workspace_bytes(ctypes.byref(shape), int(max_q_len)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("star_attn tensors must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise StarAttnError(rc, status_string(rc))
+
+
+def alloc_cache(shape: StarShape, device="cuda"):
+    """Caller-owned K/V caches [B, Hkv, cache_capacity, d] in the shape's dtype."""
+    dt = torch.float32 if shape.dtype == F32 else torch.bfloat16
+    dims = (shape.batch, shape.n_kv_heads, shape.cache_capacity, shape.head_dim)
+    return torch.zeros(dims, dtype=dt, device=device), torch.zeros(dims, dtype=dt, device=device)
+
+
+def alloc_workspace(shape: StarShape, max_q_len: int, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(shape, max_q_len)
+    if n == 0:
+        raise StarAttnError(-1, "invalid shape for workspace query")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def phase1(shape: StarShape, Q, K, V, O_ctx, K_cache, V_cache, LSE_ctx=None,
+           workspace=None, stream=None) -> None:
+    """star_attn_phase1: context encoding; fills O_ctx, the caches and LSE_ctx."""
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load_library().star_attn_phase1(
+        ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O_ctx), _ptr(LSE_ctx),
+        _ptr(K_cache), _ptr(V_cache), _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)
+
+
+def phase2(shape: StarShape, cache_len: int, Qq, Kq, Vq, K_cache, V_cache, O, workspace,
+           O_part=None, LSE_part=None, stream=None) -> None:
+    """star_attn_phase2: appends Kq/Vq at cache_len, then global attention of the
+    q_len = Qq.shape[1] new tokens; fills O (and the per-part outputs if given)."""
+    q_len = Qq.shape[1]
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load_library().star_attn_phase2(
+        ctypes.byref(shape), int(cache_len), int(q_len), _ptr(Qq), _ptr(Kq), _ptr(Vq),
+        _ptr(K_cache), _ptr(V_cache), _ptr(O_part), _ptr(LSE_part), _ptr(O),
+        _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)

@@ -1,0 +1,205 @@
+// C-ABI entry points of libstarattn: argument validation, the phase-2 split
+// plan, and kernel dispatch.  All checks run on the host before anything is
+// enqueued; no exception or HIP error state leaves these functions.
+#include "../../include/star_attn.h"
+#include "star_internal.h"
+
+#include <math.h>
+
+namespace star {
+
+static int validate_shape(const star_attn_shape* s) {
+  if (!s) return STAR_ATTN_ERR_NULL_POINTER;
+  if (s->dtype != STAR_ATTN_F32 && s->dtype != STAR_ATTN_BF16) return STAR_ATTN_ERR_UNSUPPORTED_DTYPE;
+  if (s->batch <= 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0 ||
+      s->ctx_len <= 0 || s->block <= 0 || s->cache_capacity <= 0)
+    return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (s->n_q_heads % s->n_kv_heads != 0) return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (s->n_q_heads > 65535 || s->batch > 65535) return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (s->dtype == STAR_ATTN_F32) {
+    if (s->head_dim != 64 && s->head_dim != 128) return STAR_ATTN_ERR_UNSUPPORTED_HEAD_DIM;
+  } else {
+    if (s->head_dim != 128) return STAR_ATTN_ERR_UNSUPPORTED_HEAD_DIM;
+  }
+  if (s->anchor < 0 || s->anchor > s->block) return STAR_ATTN_ERR_ANCHOR_GT_BLOCK;
+  if (s->cache_capacity < s->ctx_len) return STAR_ATTN_ERR_CACHE_OVERFLOW;
+  if (!(s->softmax_scale >= 0.f) || isinf(s->softmax_scale)) return STAR_ATTN_ERR_INVALID_SHAPE;
+  return STAR_ATTN_OK;
+}
+
+static Geom make_geom(const star_attn_shape* s) {
+  Geom g;
+  g.B = s->batch; g.Hq = s->n_q_heads; g.Hkv = s->n_kv_heads; g.G = g.Hq / g.Hkv; g.d = s->head_dim;
+  g.L = s->ctx_len; g.b = s->block; g.a = s->anchor; g.cap = s->cache_capacity;
+  g.scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+  return g;
+}
+
+static int64_t ceil_div(int64_t x, int64_t y) { return (x + y - 1) / y; }
+static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
+
+// Heads of one KV group that share a workgroup in the bf16 row-tiled kernels.
+int heads_per_workgroup(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
+
+// Split plan for a phase-2 call with q_len new tokens.  Decode-sized calls
+// (G * q_len rows fit one 16-column MFMA tile) stream the cache with many short
+// splits so that every CU has loads in flight; larger calls are compute-bound
+// and use as few splits as still fill the GPU.
+static bool make_plan(const star_attn_shape* s, int64_t q_len, SplitPlan* p) {
+  Geom g = make_geom(s);
+  int64_t n = ceil_div(g.L, g.b);
+  int64_t bmax = g.b < g.L ? g.b : g.L;
+  int64_t tail_cap = g.cap - g.L;
+  int64_t rows = (int64_t)g.G * q_len;
+  p->decode = (s->dtype == STAR_ATTN_BF16 && rows <= 16) ? 1 : 0;
+  int64_t split_len;
+  if (p->decode) {
+    int64_t key_heads = g.cap * g.B * g.Hkv;
+    int64_t want = ceil_div(key_heads, 2048);
+    split_len = 256;
+    while (split_len < want && split_len < 4096) split_len *= 2;
+  } else {
+    int64_t wgs;   // workgroups per split
+    if (s->dtype == STAR_ATTN_F32) {
+      wgs = (int64_t)g.B * g.Hq * ceil_div(q_len, 64);
+    } else {
+      int hpw = heads_per_workgroup(g.G);
+      wgs = (int64_t)g.B * g.Hkv * (g.G / hpw) * ceil_div(q_len, 128 / hpw);
+    }
+    int64_t spb = ceil_div(1024, wgs * n);
+    int64_t spb_max = bmax / 256 > 1 ? bmax / 256 : 1;
+    if (spb > spb_max) spb = spb_max;
+    if (spb < 1) spb = 1;
+    split_len = round_up(ceil_div(bmax, spb), 64);
+  }
+  int64_t spb = ceil_div(bmax, split_len);
+  int64_t st = tail_cap > 0 ? ceil_div(tail_cap, split_len) : 1;
+  int64_t s_total = n * spb + st;
+  if (s_total > (1 << 24) || n > (1 << 24)) return false;
+  p->split_len = split_len;
+  p->spb = (int32_t)spb;
+  p->st = (int32_t)st;
+  p->n_blocks = (int32_t)n;
+  p->s_total = (int32_t)s_total;
+  return true;
+}
+
+static size_t plan_bytes(const star_attn_shape* s, const SplitPlan& p, int64_t q_len) {
+  size_t rows = (size_t)s->batch * (size_t)p.s_total * (size_t)s->n_q_heads * (size_t)q_len;
+  size_t bytes = rows * (size_t)(s->head_dim + 1) * sizeof(float);
+  return (bytes + 255) & ~(size_t)255;
+}
+
+static bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace star
+
+using namespace star;
+
+extern "C" {
+
+size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len) {
+  if (validate_shape(shape) != STAR_ATTN_OK || max_q_len <= 0) return 0;
+  // The plan depends on q_len only through the number of row tiles, so the
+  // largest requirement is found at tile boundaries and at max_q_len itself.
+  size_t best = 0;
+  auto consider = [&](int64_t q) {
+    if (q < 1 || q > max_q_len) return;
+    SplitPlan p;
+    if (!make_plan(shape, q, &p)) return;
+    size_t b = plan_bytes(shape, p, q);
+    if (b > best) best = b;
+  };
+  for (int64_t q = 1; q <= max_q_len && q <= 64; ++q) consider(q);
+  for (int64_t q = 64; q <= max_q_len; q += 32) { consider(q); consider(q + 1); }
+  consider(max_q_len);
+  return best;
+}
+
+int star_attn_phase1(const star_attn_shape* shape, const void* Q, const void* K, const void* V,
+                     void* O_ctx, float* LSE_ctx, void* K_cache, void* V_cache,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  int rc = validate_shape(shape);
+  if (rc != STAR_ATTN_OK) return rc;
+  if (!Q || !K || !V || !O_ctx || !K_cache || !V_cache) return STAR_ATTN_ERR_NULL_POINTER;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O_ctx) ||
+      misaligned(K_cache) || misaligned(V_cache) || ((uintptr_t)LSE_ctx & 3u))
+    return STAR_ATTN_ERR_MISALIGNED;
+  Geom g = make_geom(shape);
+  hipStream_t st = (hipStream_t)hip_stream;
+  // Algorithm 1: keep the K/V of every block once (anchor copies never exist here).
+  if (launch_cache_write(g, shape->dtype, K, V, K_cache, V_cache, g.L, 0, st) != hipSuccess)
+    return STAR_ATTN_ERR_LAUNCH_FAILED;
+  Phase1Args a;
+  a.g = g; a.Q = Q; a.O = O_ctx; a.LSE = LSE_ctx; a.Kc = K_cache; a.Vc = V_cache;
+  hipError_t e = shape->dtype == STAR_ATTN_F32 ? launch_phase1_f32(a, st) : launch_phase1_bf16(a, st);
+  return e == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
+}
+
+int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
+                     const void* Qq, const void* Kq, const void* Vq,
+                     void* K_cache, void* V_cache, float* O_part, float* LSE_part, void* O,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = validate_shape(shape);
+  if (rc != STAR_ATTN_OK) return rc;
+  if (q_len <= 0 || q_len > (1 << 20) || cache_len < shape->ctx_len) return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (cache_len + q_len > shape->cache_capacity) return STAR_ATTN_ERR_CACHE_OVERFLOW;
+  if (!Qq || !Kq || !Vq || !K_cache || !V_cache || !O || !workspace) return STAR_ATTN_ERR_NULL_POINTER;
+  if ((O_part == nullptr) != (LSE_part == nullptr)) return STAR_ATTN_ERR_NULL_POINTER;
+  if (misaligned(Qq) || misaligned(Kq) || misaligned(Vq) || misaligned(K_cache) ||
+      misaligned(V_cache) || misaligned(O) || misaligned(O_part) || ((uintptr_t)LSE_part & 3u) ||
+      ((uintptr_t)workspace & 255u))
+    return STAR_ATTN_ERR_MISALIGNED;
+  SplitPlan plan;
+  if (!make_plan(shape, q_len, &plan)) return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (workspace_bytes < plan_bytes(shape, plan, q_len)) return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
+  Geom g = make_geom(shape);
+  if ((int64_t)g.B * plan.s_total * ((q_len + 31) / 32) * g.Hq > (int64_t)0x7fffffff)
+    return STAR_ATTN_ERR_INVALID_SHAPE;
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  // Algorithm 2: the new tokens' K/V join the cache before they attend.
+  if (launch_cache_write(g, shape->dtype, Kq, Vq, K_cache, V_cache, q_len, cache_len, st) != hipSuccess)
+    return STAR_ATTN_ERR_LAUNCH_FAILED;
+
+  size_t rows = (size_t)g.B * plan.s_total * g.Hq * (size_t)q_len;
+  Phase2Args a;
+  a.g = g; a.plan = plan; a.cache_len = cache_len; a.q_len = (int32_t)q_len;
+  a.Qq = Qq; a.Kc = K_cache; a.Vc = V_cache;
+  a.O_sub = (float*)workspace;
+  a.LSE_sub = (float*)workspace + rows * g.d;
+  hipError_t e;
+  if (shape->dtype == STAR_ATTN_F32) e = launch_phase2_f32(a, st);
+  else if (plan.decode) e = launch_phase2_decode_bf16(a, st);
+  else e = launch_phase2_rows_bf16(a, st);
+  if (e != hipSuccess) return STAR_ATTN_ERR_LAUNCH_FAILED;
+
+  MergeArgs m;
+  m.g = g; m.plan = plan; m.q_len = (int32_t)q_len; m.out_bf16 = shape->dtype == STAR_ATTN_BF16;
+  m.O_sub = a.O_sub; m.LSE_sub = a.LSE_sub; m.O_part = O_part; m.LSE_part = LSE_part; m.O = O;
+  return launch_merge(m, st) == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
+}
+
+const char* star_attn_status_string(int status) {
+  switch (status) {
+    case STAR_ATTN_OK: return "ok";
+    case STAR_ATTN_ERR_INVALID_SHAPE: return "invalid shape";
+    case STAR_ATTN_ERR_NULL_POINTER: return "required pointer is NULL";
+    case STAR_ATTN_ERR_UNSUPPORTED_HEAD_DIM: return "unsupported head_dim";
+    case STAR_ATTN_ERR_UNSUPPORTED_DTYPE: return "unsupported dtype";
+    case STAR_ATTN_ERR_ANCHOR_GT_BLOCK: return "anchor outside [0, block]";
+    case STAR_ATTN_ERR_CACHE_OVERFLOW: return "cache capacity exceeded";
+    case STAR_ATTN_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case STAR_ATTN_ERR_LAUNCH_FAILED: return "kernel launch failed";
+    case STAR_ATTN_ERR_MISALIGNED: return "pointer not sufficiently aligned";
+    default: return "unknown status";
+  }
+}
+
+const char* star_attn_kernel_path(const star_attn_shape* shape) {
+  if (validate_shape(shape) != STAR_ATTN_OK) return nullptr;
+  return shape->dtype == STAR_ATTN_F32 ? "f32-valu" : "bf16-mfma";
+}
+
+}  // extern "C"

@@ -1,0 +1,248 @@
+// bf16 split-KV partial attention for decode-sized phase-2 calls (head_dim 128,
+// G * q_len <= 16 rows per KV head): Eq. 1-2 evaluated per split of the cache.
+//
+// A decode step reads every cached K and V byte exactly once and does 4-8 flops
+// per byte, so the kernel is built as an HBM stream:
+//   * one wavefront per workgroup, one split (a contiguous run of keys of one
+//     KV head) per workgroup; thousands of independent workgroups, no barriers;
+//   * the wavefront DMAs 32-key steps of K and V (8 KiB each) straight into a
+//     two-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
+//     bursts, no VGPRs held by data in flight -- and waits with partial vmcnt so
+//     the next step is always in flight while the current one is consumed;
+//   * all G query heads of the KV group (and up to 16/G new tokens) form the 16
+//     columns of v_mfma_f32_16x16x32_bf16, so K and V are read once per KV head;
+//     S^T = K Q^T leaves each lane with keys of one query column, and the
+//     exponentiated tile is directly the B operand of O^T += V^T P^T, with V^T
+//     fragments from the LDS transposing read;
+//   * 16-byte chunks of a key row are rotated-XOR swizzled in LDS so both operand
+//     reads are conflict-free.
+// Each workgroup writes its split's normalised output rows and their
+// log-sum-exp; the merge kernel folds the splits (Eq. 3-4).
+#include "star_internal.h"
+
+namespace star {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+constexpr int D = 128;
+constexpr int ROWB = D * 2;
+constexpr int STEP = 32;                 // keys per pipeline step
+constexpr int STEPB = STEP * ROWB;       // 8 KiB of K (and of V) per step
+constexpr int LDS_K0 = 0, LDS_V0 = STEPB, LDS_K1 = 2 * STEPB, LDS_V1 = 3 * STEPB;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+#define LDS_AS __attribute__((address_space(3)))
+
+// chunk c of key row r sits in slot c ^ swz(r)
+__device__ __forceinline__ int swz(int r) { return ((r << 1) & 15) | ((r >> 3) & 1); }
+
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(gptr), "s"(lds_base) : "memory");
+}
+
+__device__ __forceinline__ float xor16(float x) {
+  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401F));
+}
+__device__ __forceinline__ float xor32_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xor32_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+struct DecState {
+  bf16x8 q[4];     // Q^T fragments: q[t] = Q[column lane%16][32t + 8*(lane/16) .. +7]
+  f32x4 o[8];      // O^T: o[dt][v] = O[column][16dt + 4*(lane/16) + v]
+  float m, l;
+};
+
+// DMA one 32-key step of K and V.  Instruction `it` moves rows 4it..4it+3; lane
+// L moves (row 4it + L/16, slot L%16).  Rows past `hi` re-read the last valid row.
+__device__ __forceinline__ void issue_step(const char* Kb, const char* Vb, int key0, int hi,
+                                           unsigned ldsK, unsigned ldsV, int lane,
+                                           const int (&coff)[4]) {
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    int key = key0 + 4 * it + (lane >> 4);
+    key = key < hi ? key : hi - 1;
+    size_t off = (size_t)key * ROWB + coff[it & 3];
+    dma16(Kb + off, ldsK + it * 1024);
+    dma16(Vb + off, ldsV + it * 1024);
+  }
+}
+
+template <int KOFF, int VOFF>
+__device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr)[4],
+                                             const unsigned (&vaddr)[8], int key0, int lim,
+                                             bool masked, float c, int j4) {
+  f32x4 s[2];
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+    s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      bf16x8 a = *(LDS_AS bf16x8*)(kaddr[t] + KOFF + kt * 16 * ROWB);
+      s[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, w.q[t], s[kt], 0, 0, 0);
+    }
+  }
+  if (masked) {
+    int x = lim - key0 - 4 * j4;     // element (kt, v) is key key0 + 16kt + 4*j4 + v
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) s[kt][v] = (16 * kt + v) < x ? s[kt][v] : -INFINITY;
+  }
+  float tmax = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                     fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+  tmax = fmaxf(tmax, xor16(tmax));
+  tmax = xor32_max(tmax);
+  float m_new = fmaxf(w.m, tmax);
+  if (__builtin_amdgcn_ballot_w64(m_new > w.m) != 0) {
+    float mm = m_new == -INFINITY ? 0.f : m_new;
+    float alpha = __builtin_amdgcn_exp2f((w.m - mm) * c);
+    w.l *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) w.o[dt] *= alpha;
+    w.m = m_new;
+  }
+  float neg_mc = (w.m == -INFINITY ? 0.f : w.m) * -c;
+  bf16x8 p;
+  float lsum = 0.f;
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][v], c, neg_mc));
+      lsum += e;
+      p[4 * kt + v] = (__bf16)e;
+    }
+  w.l += lsum;
+  // B operand slot e of lane group j4 is key 16(e/4) + 4*j4 + e%4; the A operand
+  // (V^T, d-row lane%16) takes keys 4*j4..+3 and 16 + 4*j4..+3 from two
+  // transposing reads.
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) {
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(vaddr[dt] + VOFF));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(vaddr[dt] + VOFF + 16 * ROWB));
+    bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo), hi_b = __builtin_bit_cast(bf16x4, hi);
+    bf16x8 a = __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
+    w.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, p, w.o[dt], 0, 0, 0);
+  }
+}
+
+// grid: x = split, y = kv head, z = batch; 64 threads
+__global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
+  __shared__ __attribute__((aligned(1024))) char lds[4 * STEPB];
+  const Geom& g = a.g;
+  const int lane = threadIdx.x;
+  const int qc = lane & 15, j4 = lane >> 4;
+  const int sp = blockIdx.x, kvh = blockIdx.y, beta = blockIdx.z;
+  const int R = g.G * a.q_len;                 // <= 16 live columns
+  const int j = qc / g.G, head = kvh * g.G + qc % g.G;
+  const bool live = qc < R;
+
+  int total = (int)(a.cache_len + a.q_len);
+  int64_t lo64, hi64;
+  split_range(a.plan, g.L, g.b, total, sp, &lo64, &hi64);
+  const int lo = (int)lo64, hi = (int)hi64;
+  size_t r = (((size_t)beta * a.plan.s_total + sp) * g.Hq + head) * a.q_len + j;
+  if (lo >= hi) {                              // empty split (short block, unused tail)
+    if (live && j4 == 0) a.LSE_sub[r] = -INFINITY;
+    return;
+  }
+
+  DecState w;
+  {
+    const char* qrow = (const char*)a.Qq + (((size_t)beta * a.q_len + (live ? j : 0)) * g.Hq +
+                                            (live ? head : kvh * g.G)) * ROWB;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      bf16x8 v = *(const bf16x8*)(qrow + (32 * t + 8 * j4) * 2);
+      if (!live) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      w.q[t] = v;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) w.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    w.m = -INFINITY;
+    w.l = 0.f;
+  }
+  const unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
+  // K operand: lane (i = lane%16, j4) reads row i, chunk 4t + j4
+  unsigned kaddr[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) kaddr[t] = lds0 + qc * ROWB + (((4 * t + j4) ^ swz(qc)) << 4);
+  // V^T operand: source lane addresses row 4*j4 + (lane%16)/4 (+16 for the second
+  // read), columns 16dt + 4*(lane%4) .. +3
+  unsigned vaddr[8];
+  {
+    int rr = 4 * j4 + (qc >> 2);
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+      vaddr[dt] = lds0 + rr * ROWB + (((2 * dt + ((lane & 3) >> 1)) ^ swz(rr)) << 4) + 8 * (lane & 1);
+  }
+  int coff[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) coff[it] = ((lane & 15) ^ swz(4 * it + (lane >> 4))) << 4;
+
+  const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
+  const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
+  const float c = g.scale * LOG2E;
+  // token j sees cache rows [0, cache_len + j]; only splits that reach past
+  // cache_len (the tail) or end inside a step need the masking path
+  const int row_lim = live ? (int)a.cache_len + j + 1 : 0;
+  const int lim = row_lim < hi ? row_lim : hi;
+  const int free_hi = (int)a.cache_len + 1 < hi ? (int)a.cache_len + 1 : hi;  // keys below are visible to every live row
+
+  const int nsteps = (hi - lo + STEP - 1) / STEP;
+  issue_step(Kb, Vb, lo, hi, lds0 + LDS_K0, lds0 + LDS_V0, lane, coff);
+  if (nsteps > 1) issue_step(Kb, Vb, lo + STEP, hi, lds0 + LDS_K1, lds0 + LDS_V1, lane, coff);
+  for (int s = 0; s < nsteps; s += 2) {
+    int key0 = lo + s * STEP;
+    if (s + 1 < nsteps) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    compute_step<LDS_K0, LDS_V0>(w, kaddr, vaddr, key0, lim, key0 + STEP > free_hi, c, j4);
+    if (s + 1 >= nsteps) break;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // ring slot 0 fully read
+    if (s + 2 < nsteps) {
+      issue_step(Kb, Vb, key0 + 2 * STEP, hi, lds0 + LDS_K0, lds0 + LDS_V0, lane, coff);
+      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    compute_step<LDS_K1, LDS_V1>(w, kaddr, vaddr, key0 + STEP, lim, key0 + 2 * STEP > free_hi, c, j4);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // ring slot 1 fully read
+    if (s + 3 < nsteps)
+      issue_step(Kb, Vb, key0 + 3 * STEP, hi, lds0 + LDS_K1, lds0 + LDS_V1, lane, coff);
+  }
+
+  float l_tot = w.l + xor16(w.l);
+  l_tot = xor32_sum(l_tot);
+  if (live) {
+    float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    float* orow = a.O_sub + r * D;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) *(f32x4*)(orow + 16 * dt + 4 * j4) = w.o[dt] * inv;
+    if (j4 == 0)
+      a.LSE_sub[r] = l_tot > 0.f ? (w.m * c + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_phase2_decode_bf16(const Phase2Args& a, hipStream_t st) {
+  const Geom& g = a.g;
+  if (g.Hkv > 65535 || g.B > 65535) return hipErrorInvalidValue;
+  decode_bf16_kernel<<<dim3((unsigned)a.plan.s_total, (unsigned)g.Hkv, (unsigned)g.B), 64, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace star

@@ -1,0 +1,97 @@
+// Internal declarations shared by the translation units of libstarattn.
+// Nothing here is part of the public ABI (see include/star_attn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace star {
+
+// ---------------------------------------------------------------------------
+// Phase-2 split plan: every part of the cache (one per context block, plus the
+// tail) is cut into `splits of split_len keys`; a split never straddles a part
+// boundary, so per-part results can be rebuilt from whole splits.
+// Split index s in [0, n_blocks * spb) is context block s / spb, piece s % spb;
+// indices from n_blocks * spb on are pieces of the tail.
+// ---------------------------------------------------------------------------
+struct SplitPlan {
+  int64_t split_len;   // keys per split (multiple of 64)
+  int32_t spb;         // splits per context block
+  int32_t st;          // splits for the tail [L, cache_capacity)
+  int32_t n_blocks;    // n = ceil(L / b)
+  int32_t s_total;     // n_blocks * spb + st
+  int32_t decode;      // 1: streaming split-KV kernel, 0: row-tiled kernel
+};
+
+// Geometry every kernel needs.  Strides are in elements.
+struct Geom {
+  int32_t B, Hq, Hkv, G, d;
+  int64_t L, b, a, cap;
+  float scale;          // softmax scale (natural units)
+};
+
+struct Phase1Args {
+  Geom g;
+  const void* Q;        // [B, L, Hq, d]
+  void* O;              // [B, L, Hq, d]
+  float* LSE;           // [B, Hq, L] or null
+  const void* Kc;       // caches [B, Hkv, cap, d], already holding the context
+  const void* Vc;
+};
+
+struct Phase2Args {
+  Geom g;
+  SplitPlan plan;
+  int64_t cache_len;    // tokens cached before this call
+  int32_t q_len;
+  const void* Qq;       // [B, q_len, Hq, d]
+  const void* Kc;       // caches, new tokens already appended
+  const void* Vc;
+  float* O_sub;         // [B, s_total, Hq, q_len, d]   per-split local attention
+  float* LSE_sub;       // [B, s_total, Hq, q_len]      per-split log-sum-exp
+};
+
+struct MergeArgs {
+  Geom g;
+  SplitPlan plan;
+  int32_t q_len;
+  int32_t out_bf16;
+  const float* O_sub;
+  const float* LSE_sub;
+  float* O_part;        // [B, n+1, Hq, q_len, d] or null
+  float* LSE_part;      // [B, n+1, Hq, q_len] or null
+  void* O;              // [B, q_len, Hq, d]
+};
+
+// Key range [lo, hi) of split s (hi clipped to what exists for this call).
+__host__ __device__ inline void split_range(const SplitPlan& p, int64_t L, int64_t b,
+                                            int64_t total_keys, int s, int64_t* lo, int64_t* hi) {
+  int n_ctx = p.n_blocks * p.spb;
+  if (s < n_ctx) {
+    int64_t m = s / p.spb, piece = s % p.spb;
+    int64_t blo = m * b, bhi = (m + 1) * b < L ? (m + 1) * b : L;
+    int64_t x = blo + piece * p.split_len;
+    int64_t y = x + p.split_len;
+    *lo = x < bhi ? x : bhi;
+    *hi = y < bhi ? y : bhi;
+  } else {
+    int64_t x = L + (int64_t)(s - n_ctx) * p.split_len;
+    int64_t y = x + p.split_len;
+    *lo = x < total_keys ? x : total_keys;
+    *hi = y < total_keys ? y : total_keys;
+  }
+}
+
+// Host-side launchers (each returns the hipError_t of its launch).
+hipError_t launch_cache_write(const Geom& g, int dtype, const void* K, const void* V,
+                              void* Kc, void* Vc, int64_t n_tokens, int64_t dst_row,
+                              hipStream_t st);
+hipError_t launch_phase1_f32(const Phase1Args& a, hipStream_t st);
+hipError_t launch_phase2_f32(const Phase2Args& a, hipStream_t st);
+hipError_t launch_phase1_bf16(const Phase1Args& a, hipStream_t st);
+hipError_t launch_phase2_rows_bf16(const Phase2Args& a, hipStream_t st);
+hipError_t launch_phase2_decode_bf16(const Phase2Args& a, hipStream_t st);
+hipError_t launch_merge(const MergeArgs& a, hipStream_t st);
+
+}  // namespace star

@@ -1,0 +1,85 @@
+"""GPU parity: the HIP path (called through the C ABI) against the fp64 oracle
+on the same seeded inputs.  Tolerances: max-abs 1e-5 (fp32) / 2e-2 (bf16) on
+outputs, 1e-5 / 1e-2 on log-sum-exps; caches bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from tests import parity_harness as ph
+
+pytestmark = pytest.mark.gpu
+
+
+def _report(rep):
+    print(f"\n[{rep.name}] {rep.detail}", flush=True)
+    assert rep.ok, rep.detail
+
+
+def test_config1_fp32_every_row():
+    """Config 1 in full: every row, head and decode step."""
+    _report(ph.run_parity(workloads.CONFIGS["C1"], all_rows=True, verbose=True))
+
+
+@pytest.mark.parametrize("L,b,a,lq,nd", [
+    (1000, 256, 256, 5, 3),      # ragged last block
+    (777, 200, 37, 70, 2),       # nothing tile-aligned, anchor < block, two row tiles
+    (300, 512, 512, 3, 1),       # single block: full causal attention
+    (640, 128, 0, 9, 2),         # no anchor
+])
+def test_fp32_odd_shapes(L, b, a, lq, nd):
+    cfg = workloads.StarConfig("f32odd", "fp32", 2, 4, 2, 64, L, b, a, lq, nd, seed=L + b)
+    _report(ph.run_parity(cfg, all_rows=True))
+
+
+def test_fp32_head_dim_128():
+    cfg = workloads.StarConfig("f32d128", "fp32", 1, 2, 1, 128, 500, 128, 64, 33, 2, seed=9)
+    _report(ph.run_parity(cfg, all_rows=True))
+
+
+@pytest.mark.parametrize("Hq,Hkv,L,b,a,lq,nd", [
+    (4, 1, 2048, 512, 512, 40, 3),     # G = 4: four heads per workgroup
+    (8, 1, 1500, 400, 100, 130, 2),    # G = 8, ragged everything, anchor < block
+    (2, 2, 1024, 256, 256, 64, 2),     # G = 1: one head, 128 tokens per workgroup
+    (6, 3, 900, 300, 0, 17, 2),        # G = 2, no anchor
+    (4, 1, 700, 1024, 1024, 5, 4),     # single block (block > context)
+])
+def test_bf16_small_every_row(Hq, Hkv, L, b, a, lq, nd):
+    """Small bf16 shapes compared on every row: several row tiles, several key
+    tiles, ragged tails, every GQA packing."""
+    cfg = workloads.StarConfig("bf16small", "bf16", 2, Hq, Hkv, 128, L, b, a, lq, nd,
+                               seed=Hq * 1000 + L, n_planted=4)
+    _report(ph.run_parity(cfg, all_rows=True))
+
+
+def test_config2_bf16_sampled():
+    _report(ph.run_parity(workloads.CONFIGS["C2"], verbose=True))
+
+
+def test_config3_bf16_sampled():
+    _report(ph.run_parity(workloads.CONFIGS["C3"], verbose=True))
+
+
+def test_config5_bf16_sampled():
+    _report(ph.run_parity(workloads.CONFIGS["C5"], n_random=128, decode_samples=3, verbose=True))
+
+
+def test_config4_bf16_sampled():
+    _report(ph.run_parity(workloads.CONFIGS["C4"], n_random=96, decode_samples=2, verbose=True))
+
+
+def test_run_to_run_determinism():
+    """Same inputs, same bits (no floating-point atomics anywhere)."""
+    cfg = workloads.StarConfig("det", "bf16", 1, 8, 2, 128, 4096, 1024, 1024, 48, 2, seed=3)
+    inp = workloads.make_inputs(cfg, "cuda")
+    outs = []
+    for _ in range(2):
+        run = ph.HipRun(cfg, inp)
+        run.phase1()
+        O, Op, Lp = run.phase2(inp.Qq, inp.Kq, inp.Vq)
+        O1, _, _ = run.phase2(inp.Qd[:, :1].contiguous(), inp.Kd[:, :1].contiguous(),
+                              inp.Vd[:, :1].contiguous(), want_parts=False)
+        torch.cuda.synchronize()
+        outs.append((run.O_ctx.clone(), run.LSE_ctx.clone(), O, Op, Lp, O1))
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
