@@ -85,18 +85,22 @@ class Timer:
         return e0.elapsed_time(e1)
 
 
-def run_step(cfg, shape, inp, bufs, timer):
-    """One pass of the hot path; returns event indices (phase1, query, [decode...])."""
+def run_step(cfg, shape, inp, bufs, timer, sections=("phase1", "query", "decode")):
+    """One pass of the hot path; returns event indices (phase1, query, [decode...]).
+    `sections` exists for profiling runs that isolate one part; the default (and
+    the only thing the reported numbers use) is the whole path."""
     e = timer.start()
-    sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+    if "phase1" in sections:
+        sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
     i_p1 = timer.stop(e)
     cache_len = cfg.L
     e = timer.start()
-    sa.phase2(shape, cache_len, inp.Qq, inp.Kq, inp.Vq, bufs["Kc"], bufs["Vc"], bufs["Oq"], bufs["ws"])
+    if "query" in sections:
+        sa.phase2(shape, cache_len, inp.Qq, inp.Kq, inp.Vq, bufs["Kc"], bufs["Vc"], bufs["Oq"], bufs["ws"])
     i_q = timer.stop(e)
     cache_len += cfg.lq
     i_d = []
-    for t in range(cfg.nd):
+    for t in range(cfg.nd if "decode" in sections else 0):
         e = timer.start()
         sa.phase2(shape, cache_len, bufs["Qd"][t], bufs["Kd"][t], bufs["Vd"][t], bufs["Kc"], bufs["Vc"],
                   bufs["Od"][t], bufs["ws"])
@@ -150,6 +154,8 @@ def main():
     ap.add_argument("--config", default="C3", choices=sorted(workloads.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-causal", action="store_true")
+    ap.add_argument("--sections", default="phase1,query,decode",
+                    help="profiling aid: comma list of phase1,query,decode to run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the hot path of one GPU's share); "
@@ -173,14 +179,15 @@ def main():
         "Vd": [inp.Vd[:, t:t + 1].contiguous() for t in range(cfg.nd)],
         "Od": [torch.empty_like(inp.Qd[:, :1]) for _ in range(cfg.nd)],
     }
+    sections = tuple(args.sections.split(","))
     timer = Timer()
     for _ in range(args.warmup):
-        run_step(cfg, shape, inp, bufs, timer)
+        run_step(cfg, shape, inp, bufs, timer, sections)
     torch.cuda.synchronize()
     timer.pairs.clear()
     t0 = time.perf_counter()
     e_all = timer.start()
-    recs = [run_step(cfg, shape, inp, bufs, timer) for _ in range(args.steps)]
+    recs = [run_step(cfg, shape, inp, bufs, timer, sections) for _ in range(args.steps)]
     i_all = timer.stop(e_all)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -226,6 +233,8 @@ def main():
                                     "decode call (append + split-KV + merge)"},
         "wall_ms_per_step": wall_ms / args.steps,
     }
+    if sections != ("phase1", "query", "decode"):
+        out["sections"] = list(sections)   # partial run: not a reportable result
 
     if not args.no_full_causal and cfg.name != "C4":
         fshape = sa.StarShape.make(cfg.dtype, cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.L, cfg.L,

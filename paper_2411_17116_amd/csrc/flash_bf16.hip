@@ -54,19 +54,21 @@ constexpr float LN2 = 0.6931471805599453f;
 // chunk swizzle of a key row: chunk c of row r is stored in slot c ^ swz(r)
 __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
-// 16-byte DMA global -> LDS: lane L's data lands at lds_base + 16 * L.
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(gptr), "s"(lds_base) : "memory");
+// 16-byte DMA global -> LDS: lane L's data lands at lds_base + 16 * L.  The
+// global address is sbase + voff (unsigned 32-bit byte offset per lane).
+__device__ __forceinline__ void dma16(const char* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
 }
 
 __device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
   return *(LDS_AS bf16x8*)(addr);
 }
 
-// Transposing LDS read; see the V^T fragment description in attend().
-__device__ __forceinline__ s16x4 lds_read_tr16(unsigned addr) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(addr));
+// Transposing LDS read: within each group of 16 lanes, lane i receives element
+// i%4 of the four 8-byte rows addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.
+__device__ __forceinline__ bf16x4 lds_read_tr16(unsigned addr) {
+  return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(addr)));
 }
 
 __device__ __forceinline__ float pair_max(float x) {
@@ -78,6 +80,9 @@ __device__ __forceinline__ float pair_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+__device__ __forceinline__ void wait_vmcnt8() { __builtin_amdgcn_s_waitcnt(0x0F78); }
 
 // Sequence of key tiles a workgroup walks: first the tiles of [0, a_hi)
 // (n_a of them), then the tiles of [loc_lo, loc_hi).
@@ -100,167 +105,260 @@ struct WaveState {
   float l;            // this lane's share of the running sum of 2^((s-m) c)
 };
 
-// Issue the DMA of one K tile and one V tile.  Thread `tid` moves the 16-byte
-// unit (row it*16 + tid/16, slot tid%16) for it = 0..3; rows past `hi` re-read
-// the last valid row (they are masked in the score tile).
-__device__ __forceinline__ void issue_tile(const char* Kb, const char* Vb, int key0, int hi,
-                                           unsigned ldsK, unsigned ldsV, int tid, int chunk_off) {
-  int wave_base = __builtin_amdgcn_readfirstlane((tid & ~63) * 16);
-  int r0 = key0 + (tid >> 4);
+// Per-lane LDS addresses and DMA offsets, fixed for the whole kernel.
+struct LaneAddr {
+  unsigned k[8];       // K operand: row lane%32, chunk 2t + lane/32 (swizzled)
+  unsigned v[4][2];    // V^T operand: see attend()
+  unsigned dma[4];     // byte offset of this thread's unit in rows it*16 + tid/16
+  int tid;
+  int half;
+};
+
+// Issue the DMA of one 64-key tile of K or V into an LDS tile buffer.  Thread
+// `tid` moves the 16-byte unit (row it*16 + tid/16, slot tid%16) for it = 0..3;
+// rows at or past `hi` re-read the last valid row (they are masked in the score
+// tile, and finite values keep 0 * V finite).
+__device__ __forceinline__ void issue_tile(const char* base, int key0, int hi, unsigned lds,
+                                           const LaneAddr& la) {
+  unsigned wave_base = __builtin_amdgcn_readfirstlane((la.tid & ~63) * 16);
+  if (key0 + TKEYS <= hi) {            // full tile: scalar base, constant lane offsets
+    const char* sb = base + (size_t)key0 * ROWB;
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    int key = r0 + it * 16;
-    key = key < hi ? key : hi - 1;
-    size_t off = (size_t)key * ROWB + chunk_off;
-    dma16(Kb + off, ldsK + it * 4096 + wave_base);
-    dma16(Vb + off, ldsV + it * 4096 + wave_base);
+    for (int it = 0; it < 4; ++it) dma16(sb, la.dma[it], lds + it * 4096 + wave_base);
+  } else {
+    int chunk_off = la.dma[0] & 255;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      int key = key0 + it * 16 + (la.tid >> 4);
+      key = key < hi ? key : hi - 1;
+      dma16(base, (unsigned)key * ROWB + chunk_off, lds + it * 4096 + wave_base);
+    }
   }
 }
 
-// One 64-key tile for one wavefront.
-//   key0        first key of the tile
-//   lim         this lane's exclusive key bound (min of the row's causal bound
-//               and the range end); only used when `masked`
-//   masked      wave-uniform: some element of the tile may be invisible
-template <int KOFF, int VOFF>
-__device__ __forceinline__ void compute_tile(WaveState& w, const unsigned (&kaddr)[8],
-                                             const unsigned (&vaddr)[4][2], int key0, int lim,
-                                             bool masked, float c, int half) {
-  f32x16 s[2];
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      bf16x8 a = lds_read_b128(kaddr[t] + KOFF + kb * 32 * ROWB);
-      s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, w.q[t], s[kb], 0, 0, 0);
-    }
-  }
-  if (masked) {
-    // element v of sub-tile kb is key key0 + 32kb + 8(v/4) + 4*half + v%4
-    int x = lim - key0 - 4 * half;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        s[kb][v] = (32 * kb + 8 * (v / 4) + (v % 4)) < x ? s[kb][v] : -INFINITY;
-  }
-  float tmax = s[0][0];
-#pragma unroll
-  for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[0][v]);
-#pragma unroll
-  for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[1][v]);
+// Online-softmax bookkeeping of one 32-key score tile (log2 domain): new row
+// maximum, the factor `alpha` by which everything accumulated so far has to be
+// rescaled (1 if the maximum did not move, 0 while nothing was visible yet) and
+// the offset -m*c for the exponentials.
+__device__ __forceinline__ void softmax_head(WaveState& w, const f32x16& s, float c, float* alpha,
+                                             float* neg_mc) {
+  float t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
+  float t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+  float t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+  float t3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+  float t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
+  float tmax = fmaxf(fmaxf(fmaxf(t0, t1), fmaxf(t2, t3)), fmaxf(t4, s[15]));
   tmax = pair_max(tmax);
   float m_new = fmaxf(w.m, tmax);
-  if (__builtin_amdgcn_ballot_w64(m_new > w.m) != 0) {      // some row maximum moved
-    float mm = m_new == -INFINITY ? 0.f : m_new;
-    float alpha = __builtin_amdgcn_exp2f((w.m - mm) * c);   // 0 while w.m == -inf
-    w.l *= alpha;
+  float mm = m_new == -INFINITY ? 0.f : m_new;
+  *alpha = __builtin_amdgcn_exp2f((w.m - mm) * c);
+  *neg_mc = mm * -c;
+  w.l *= *alpha;
+  w.m = m_new;
+}
+
+// Exponentials and bf16 conversion of 8 of the 16 scores a lane holds.
+template <int HALF>
+__device__ __forceinline__ void softmax_half(WaveState& w, const f32x16& s, bf16x8& p, float c,
+                                             float neg_mc) {
+  float lsum = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * HALF + v], c, neg_mc));
+    lsum += e;
+    p[v] = (__bf16)e;
+  }
+  w.l += lsum;
+}
+
+// Causal / range-end mask of one 32-key score tile: element v is key
+// key0 + 8(v/4) + 4*half + v%4 and is visible iff it is below `lim`.
+__device__ __forceinline__ void mask_unit(f32x16& s, int key0, int lim, int half) {
+  int x = lim - key0 - 4 * half;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) s[v] = (8 * (v / 4) + (v % 4)) < x ? s[v] : -INFINITY;
+}
+
+__device__ __forceinline__ void rescale(WaveState& w, float alpha) {
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // some row maximum moved
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) w.o[dt][v] *= alpha;
-    w.m = m_new;
   }
-  float neg_mc = (w.m == -INFINITY ? 0.f : w.m) * -c;
-  bf16x8 p[2][2];
-  float lsum = 0.f;
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], c, neg_mc));
-      lsum += e;
-      p[kb][v / 8][v % 8] = (__bf16)e;
-    }
-  w.l += lsum;
-  // O^T[32dt.., row] += V^T P^T.  For sub-tile kb and half-sub-tile cc the B
-  // operand is p[kb][cc]: slot e of lane half `half` is key
-  // 32kb + 16cc + 8(e/4) + 4*half + e%4, so the A operand needs, for d-row
-  // lane%32, keys k0..k0+3 and k0+8..k0+11 with k0 = 32kb + 16cc + 4*half.
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        s16x4 lo = lds_read_tr16(vaddr[dt][0] + VOFF + (32 * kb + 16 * cc) * ROWB);
-        s16x4 hi = lds_read_tr16(vaddr[dt][1] + VOFF + (32 * kb + 16 * cc) * ROWB);
-        bf16x8 a;
-        bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo), hi_b = __builtin_bit_cast(bf16x4, hi);
-        a = __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
-        w.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[kb][cc], w.o[dt], 0, 0, 0);
-      }
 }
 
-// Walk a tile sequence for the calling wavefront.
-//   row_lim     this lane's exclusive causal key bound (0 for an inactive row)
-//   wave_lo/hi  min / max of row_lim over the wavefront's active rows
-__device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const char* Kb,
-                                       const char* Vb, int row_lim, int wave_lo, int wave_hi,
-                                       float c, unsigned lds0) {
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int half = lane >> 5;
-  const int i32 = lane & 31;
-  // K operand: lane (i32, half) reads row i32 (+32 kb), chunk 2t + half
-  unsigned kaddr[8];
-  {
-    int x = half ^ swz(i32);
+// One pipeline stage holds three independent pieces of work:
+//   QK  : s_next  = K[unit u+1] Q^T          (8 MFMAs, K fragments from LDS at KOFF)
+//   SM  : p_cur   = softmax numerators of s_cur (unit u), updates w.m / w.l
+//   PV  : O^T    += V[unit u-1]^T p_prev      (8 MFMAs, V^T fragments from LDS at VOFF)
+// so that the MFMAs of two units hide the exponentials of the third.  The
+// sched_group_barrier sequence at the end pins the instruction order inside the
+// stage: operand fragments are read from LDS two MFMA pairs ahead of their use
+// and about five VALU instructions sit between consecutive MFMAs.
+template <bool QK, bool SM, bool PV, int KOFF, int VOFF>
+__device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16& s_next,
+                                       f32x16& s_cur, bf16x8 (&p_cur)[2],
+                                       const bf16x8 (&p_prev)[2], float c) {
+  float alpha = 1.0f, neg_mc = 0.f;
+  bf16x8 kf[8], vf[8];
+  // Keep this stage's softmax inside the stage: without the anchors the optimizer
+  // hoists it above the preceding barrier and sinks the row sums to the loop end.
+  if (SM) asm volatile("" : "+v"(s_cur));
 #pragma unroll
-    for (int t = 0; t < 8; ++t) kaddr[t] = lds0 + i32 * ROWB + (((2 * t) ^ x) << 4);
+  for (int i = 0; i < 8; ++i) {
+    if (QK) kf[i] = lds_read_b128(la.k[i] + KOFF);
+    if (PV) {
+      // B operand p_prev[hf]: slot e of lane half h is key 16hf + 8(e/4) + 4h + e%4,
+      // so the A operand needs, for d-row lane%32, keys k0..k0+3 and k0+8..k0+11
+      // with k0 = 16hf + 4h: two transposing reads.
+      const int hf = i >> 2, dt = i & 3;
+      bf16x4 lo = lds_read_tr16(la.v[dt][0] + VOFF + 16 * hf * ROWB);
+      bf16x4 hi = lds_read_tr16(la.v[dt][1] + VOFF + 16 * hf * ROWB);
+      vf[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
   }
-  // V^T operand: source lane addresses row 4*half + (lane%16)/4 (+8 for the
-  // second read), columns 32dt + 16*((lane/16)%2) + 4*(lane%4) .. +3
-  unsigned vaddr[4][2];
+  if (SM) {
+    softmax_head(w, s_cur, c, &alpha, &neg_mc);
+    softmax_half<0>(w, s_cur, p_cur[0], c, neg_mc);
+    softmax_half<1>(w, s_cur, p_cur[1], c, neg_mc);
+  }
+  if (QK) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_next[v] = 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (QK) s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], w.q[i], s_next, 0, 0, 0);
+    if (PV) w.o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[i >> 2], w.o[i & 3], 0, 0, 0);
+  }
+  if (QK && SM && PV) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+    }
+  }
+  if (SM) asm volatile("" : "+v"(w.l), "+v"(w.m), "+v"(p_cur[0]), "+v"(p_cur[1]));
+  __builtin_amdgcn_sched_barrier(0);
+  return alpha;
+}
+
+// Everything a wavefront does for key tile t once tile t's scores exist:
+//   barrier (K tile t+1 and V tile t have landed; older buffers are free),
+//   DMA of K tile t+2 and V tile t+1 into the buffers just released,
+//   stage A: scores of unit 2t+2 | softmax of unit 2t+1 | PV of unit 2t,
+//   stage B: scores of unit 2t+3 | softmax of unit 2t+2 | PV of unit 2t+1.
+// MORE = tile t+1 exists.  KN / VC are the LDS offsets of K tile t+1 and V tile t,
+// KF / VF those of the buffers that are refilled (K tile t+2, V tile t+1).
+template <bool MORE, int KN, int VC, int KF, int VF>
+__device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, const TileSeq& seq,
+                                          const char* Kb, const char* Vb, int t, int row_lim,
+                                          int wave_lo, float c, unsigned lds0, f32x16& sA,
+                                          f32x16& sB, bf16x8 (&pA)[2], bf16x8 (&pB)[2]) {
+  constexpr int H = 32 * ROWB;
+  wait_vmcnt0();
+  __builtin_amdgcn_s_barrier();
+  if (t + 2 < seq.n_tiles) {
+    int k2, h2;
+    seq.tile(t + 2, &k2, &h2);
+    issue_tile(Kb, k2, h2, lds0 + KF, la);
+  }
+  if (MORE) {
+    int nk0, nhi;
+    seq.tile(t + 1, &nk0, &nhi);
+    issue_tile(Vb, nk0, nhi, lds0 + VF, la);
+    const int nlim = row_lim < nhi ? row_lim : nhi;
+    float alpha = stage<true, true, true, KN, VC>(w, la, sA, sB, pB, pA, c);
+    rescale(w, alpha);
+    if (nk0 + 32 > wave_lo || nk0 + 32 > nhi) mask_unit(sA, nk0, nlim, la.half);
+    alpha = stage<true, true, true, KN + H, VC + H>(w, la, sB, sA, pA, pB, c);
+    rescale(w, alpha);
+    if (nk0 + 64 > wave_lo || nk0 + 64 > nhi) mask_unit(sB, nk0 + 32, nlim, la.half);
+  } else {
+    float alpha = stage<false, true, true, 0, VC>(w, la, sA, sB, pB, pA, c);
+    rescale(w, alpha);
+    stage<false, false, true, 0, VC + H>(w, la, sB, sA, pA, pB, c);
+  }
+}
+
+// Walk a tile sequence for the calling wavefront (all four wavefronts of the
+// workgroup call this with the same sequence).
+//   row_lim     this lane's exclusive causal key bound (0 for an inactive row)
+//   wave_lo     smallest row_lim among the wavefront's active rows: key tiles that
+//               end at or below it need no causal mask
+__device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const char* Kb,
+                                       const char* Vb, int row_lim, int wave_lo,
+                                       float c, unsigned lds0) {
+  LaneAddr la;
+  la.tid = threadIdx.x;
+  const int lane = la.tid & 63;
+  la.half = lane >> 5;
+  const int i32 = lane & 31;
   {
+    int x = la.half ^ swz(i32);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) la.k[t] = lds0 + i32 * ROWB + (((2 * t) ^ x) << 4);
+    // V^T operand: source lane addresses row 4*half + (lane%16)/4 (+8 for the
+    // second read), columns 32dt + 16*((lane/16)%2) + 4*(lane%4) .. +3
     int q4 = (lane & 15) >> 2, gi = (lane >> 4) & 1;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        int r = 4 * half + q4 + 8 * u;
+        int r = 4 * la.half + q4 + 8 * u;
         int chunk = 4 * dt + 2 * gi + ((lane & 3) >> 1);
-        vaddr[dt][u] = lds0 + r * ROWB + ((chunk ^ swz(r)) << 4) + 8 * (lane & 1);
+        la.v[dt][u] = lds0 + r * ROWB + ((chunk ^ swz(r)) << 4) + 8 * (lane & 1);
       }
+    unsigned chunk_off = ((la.tid & 15) ^ swz(la.tid >> 4)) << 4;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) la.dma[it] = (it * 16 + (la.tid >> 4)) * ROWB + chunk_off;
   }
-  const int chunk_off = ((tid & 15) ^ swz(tid >> 4)) << 4;
+  const int T = seq.n_tiles;
+  if (T == 0) return;
+  wait_vmcnt0();              // Q fragments are in registers before any DMA is counted
 
-  if (seq.n_tiles == 0) return;
+  constexpr int K0 = LDS_K0, K1 = LDS_K1, V0 = LDS_V0, V1 = LDS_V1, H = 32 * ROWB;
+  f32x16 sA, sB;              // score tiles of the even / odd 32-key unit
+  bf16x8 pA[2], pB[2];        // their exponentials (bf16)
   int key0, hi;
+
+  // Prologue: K tile 0, V tile 0 and K tile 1 in flight; scores of tile 0.
   seq.tile(0, &key0, &hi);
-  issue_tile(Kb, Vb, key0, hi, lds0 + LDS_K0, lds0 + LDS_V0, tid, chunk_off);
-  for (int idx = 0; idx < seq.n_tiles; idx += 2) {
-    // ---- even tile: buffers 0
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    seq.tile(idx, &key0, &hi);
-    if (idx + 1 < seq.n_tiles) {
-      int k1, h1;
-      seq.tile(idx + 1, &k1, &h1);
-      issue_tile(Kb, Vb, k1, h1, lds0 + LDS_K1, lds0 + LDS_V1, tid, chunk_off);
-    }
-    if (key0 < wave_hi) {
-      bool masked = key0 + TKEYS > wave_lo || key0 + TKEYS > hi;
-      int lim = row_lim < hi ? row_lim : hi;
-      compute_tile<LDS_K0, LDS_V0>(w, kaddr, vaddr, key0, lim, masked, c, half);
-    }
-    if (idx + 1 >= seq.n_tiles) break;
-    // ---- odd tile: buffers 1
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    seq.tile(idx + 1, &key0, &hi);
-    if (idx + 2 < seq.n_tiles) {
-      int k1, h1;
-      seq.tile(idx + 2, &k1, &h1);
-      issue_tile(Kb, Vb, k1, h1, lds0 + LDS_K0, lds0 + LDS_V0, tid, chunk_off);
-    }
-    if (key0 < wave_hi) {
-      bool masked = key0 + TKEYS > wave_lo || key0 + TKEYS > hi;
-      int lim = row_lim < hi ? row_lim : hi;
-      compute_tile<LDS_K1, LDS_V1>(w, kaddr, vaddr, key0, lim, masked, c, half);
-    }
+  issue_tile(Kb, key0, hi, lds0 + K0, la);
+  issue_tile(Vb, key0, hi, lds0 + V0, la);
+  if (T > 1) {
+    int k1, h1;
+    seq.tile(1, &k1, &h1);
+    issue_tile(Kb, k1, h1, lds0 + K1, la);
+    wait_vmcnt8();
+  } else {
+    wait_vmcnt0();
+  }
+  __builtin_amdgcn_s_barrier();
+  const int lim0 = row_lim < hi ? row_lim : hi;
+  stage<true, false, false, K0, 0>(w, la, sA, sA, pA, pA, c);
+  if (key0 + 32 > wave_lo || key0 + 32 > hi) mask_unit(sA, key0, lim0, la.half);
+  stage<true, true, false, K0 + H, 0>(w, la, sB, sA, pA, pA, c);
+  if (key0 + 64 > wave_lo || key0 + 64 > hi) mask_unit(sB, key0 + 32, lim0, la.half);
+
+  // Tile t: V tile t is consumed while K tile t+1 produces the next scores.
+  // The loop is unrolled by two so that every LDS buffer offset is an immediate
+  // and the accumulators flow through straight-line code.
+  int t = 0;
+  for (; t + 2 < T; t += 2) {
+    tile_step<true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+    tile_step<true, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+  }
+  if (T - t == 2) {
+    tile_step<true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+    tile_step<false, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+  } else {
+    tile_step<false, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
   }
 }
 
@@ -305,7 +403,6 @@ __global__ __launch_bounds__(256, 2) void phase1_bf16_kernel(Phase1Args a, int h
   int tok = tok0 + i32;
   bool active = tok < e;
   int wg_last = row0 + tm < e ? row0 + tm : e;   // exclusive bound of the workgroup's tokens
-  int wave_last = tok0 + 32 < e ? tok0 + 32 : e;
 
   const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
@@ -323,9 +420,8 @@ __global__ __launch_bounds__(256, 2) void phase1_bf16_kernel(Phase1Args a, int h
   // a row sees key k iff k < tok + 1; anchor keys always qualify (a <= b <= tok)
   int row_lim = active ? tok + 1 : 0;
   int wave_lo = tok0 < e ? tok0 + 1 : 0;
-  int wave_hi = tok0 < e ? wave_last : 0;
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend(w, seq, Kb, Vb, row_lim, wave_lo, wave_hi, g.scale * LOG2E, lds0);
+  attend(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
   float l_tot = pair_sum(w.l);
   if (active) {
@@ -387,11 +483,9 @@ __global__ __launch_bounds__(256, 2) void phase2_rows_bf16_kernel(Phase2Args a, 
   // token j sees cache rows [0, cache_len + j]
   int cl = (int)a.cache_len;
   int row_lim = active ? cl + j + 1 : 0;
-  int wave_last = j0 + 32 < a.q_len ? j0 + 32 : a.q_len;
   int wave_lo = j0 < a.q_len ? cl + j0 + 1 : 0;
-  int wave_hi = j0 < a.q_len ? cl + wave_last : 0;
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend(w, seq, Kb, Vb, row_lim, wave_lo, wave_hi, g.scale * LOG2E, lds0);
+  attend(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
   float l_tot = pair_sum(w.l);
   if (active) {
