@@ -22,8 +22,14 @@
 //     exponentiated tile is already laid out as the B operand of the second
 //     MFMA: O^T += V^T P^T, with V^T fragments produced by the LDS transposing
 //     read.  P never touches LDS.
-//   * Softmax runs in the log2 domain in fp32; the accumulator rescale is
-//     skipped (wave-uniform branch) whenever no row maximum moved in the tile.
+//   * Softmax runs in the log2 domain in fp32 against a lazily raised reference
+//     maximum: the common path is one fma + one exp per score, a packed bf16
+//     conversion and a dot2 for the row sum; the row maximum is only searched
+//     (and the accumulators rescaled) for the first unit and when a row sum shows
+//     that the reference has become stale.  O / l does not depend on the reference.
+//   * The key loop is software-pipelined per 32-key unit: the QK MFMAs of unit
+//     u+1, the exponentials of unit u and the PV MFMAs of unit u-1 share one
+//     scheduling region whose order is pinned with sched_group_barrier.
 //   * Only tiles that touch a row's causal frontier or a ragged range end take
 //     the masking path.
 #include "star_internal.h"
@@ -81,8 +87,10 @@ __device__ __forceinline__ float pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-__device__ __forceinline__ void wait_vmcnt8() { __builtin_amdgcn_s_waitcnt(0x0F78); }
+// Waits for the DMAs.  They must be opaque asm: the DMAs themselves are opaque
+// to the compiler, which would drop a builtin s_waitcnt it believes redundant.
+__device__ __forceinline__ void wait_vmcnt0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void wait_vmcnt8() { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
 
 // Sequence of key tiles a workgroup walks: first the tiles of [0, a_hi)
 // (n_a of them), then the tiles of [loc_lo, loc_hi).
@@ -101,15 +109,17 @@ struct TileSeq {
 struct WaveState {
   bf16x8 q[8];        // Q^T fragments: q[t] = Q[row lane%32][16t + 8*(lane/32) .. +7]
   f32x16 o[4];        // O^T accumulators: o[dt][v] = O[row][32dt + 8(v/4) + 4(lane/32) + v%4]
-  float m;            // running maximum of the raw logits (pair-uniform)
+  float m;            // reference maximum of the raw logits (pair-uniform); see softmax_fix
+  float neg_mc;       // -m * c (0 while m == -inf)
   float l;            // this lane's share of the running sum of 2^((s-m) c)
+  float lmax;         // largest per-unit partial row sum seen by the fast loop
 };
 
 // Per-lane LDS addresses and DMA offsets, fixed for the whole kernel.
 struct LaneAddr {
   unsigned k[8];       // K operand: row lane%32, chunk 2t + lane/32 (swizzled)
   unsigned v[4][2];    // V^T operand: see attend()
-  unsigned dma[4];     // byte offset of this thread's unit in rows it*16 + tid/16
+  unsigned dma;        // byte offset of this thread's 16-byte unit in row tid/16
   int tid;
   int half;
 };
@@ -124,9 +134,9 @@ __device__ __forceinline__ void issue_tile(const char* base, int key0, int hi, u
   if (key0 + TKEYS <= hi) {            // full tile: scalar base, constant lane offsets
     const char* sb = base + (size_t)key0 * ROWB;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) dma16(sb, la.dma[it], lds + it * 4096 + wave_base);
+    for (int it = 0; it < 4; ++it) dma16(sb + it * 16 * ROWB, la.dma, lds + it * 4096 + wave_base);
   } else {
-    int chunk_off = la.dma[0] & 255;
+    int chunk_off = la.dma & 255;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       int key = key0 + it * 16 + (la.tid >> 4);
@@ -136,47 +146,55 @@ __device__ __forceinline__ void issue_tile(const char* base, int key0, int hi, u
   }
 }
 
-// Online-softmax bookkeeping of one 32-key score tile (log2 domain): new row
-// maximum, the factor `alpha` by which everything accumulated so far has to be
-// rescaled (1 if the maximum did not move, 0 while nothing was visible yet) and
-// the offset -m*c for the exponentials.
-__device__ __forceinline__ void softmax_head(WaveState& w, const f32x16& s, float c, float* alpha,
-                                             float* neg_mc) {
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// The fast key loop keeps ONE reference maximum per row, taken from the row's
+// first 32 keys, and never rescales: p = 2^(s c - m c) against any fixed m gives
+// the same O / l.  It only has to stay finite, so the loop tracks the largest
+// per-unit row sum and, if one exceeds this limit (a score more than ~40 nats
+// above the reference), the workgroup redoes its rows with the exact online
+// softmax (SAFE mode), which searches the maximum of every unit.
+constexpr float LSUM_LIMIT = 1.152921504606846976e18f;   // 2^60
+
+__device__ __forceinline__ float unit_max(const f32x16& s) {
   float t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
   float t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
   float t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
   float t3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
   float t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
-  float tmax = fmaxf(fmaxf(fmaxf(t0, t1), fmaxf(t2, t3)), fmaxf(t4, s[15]));
-  tmax = pair_max(tmax);
-  float m_new = fmaxf(w.m, tmax);
-  float mm = m_new == -INFINITY ? 0.f : m_new;
-  *alpha = __builtin_amdgcn_exp2f((w.m - mm) * c);
-  *neg_mc = mm * -c;
-  w.l *= *alpha;
-  w.m = m_new;
+  return pair_max(fmaxf(fmaxf(fmaxf(t0, t1), fmaxf(t2, t3)), fmaxf(t4, s[15])));
 }
 
-// Exponentials and bf16 conversion of 8 of the 16 scores a lane holds.
-template <int HALF>
-__device__ __forceinline__ void softmax_half(WaveState& w, const f32x16& s, bf16x8& p, float c,
-                                             float neg_mc) {
+// Softmax numerators of one 32-key score tile against the reference w.m:
+// p = 2^(s c - m c) rounded to bf16, and the lane's sum of the ROUNDED values
+// (v_dot2 with a vector of ones), so numerator and denominator see the same
+// rounding.
+__device__ __forceinline__ float softmax_unit(const WaveState& w, const f32x16& s, bf16x8 (&p)[2],
+                                              float c) {
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   float lsum = 0.f;
 #pragma unroll
-  for (int v = 0; v < 8; ++v) {
-    float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * HALF + v], c, neg_mc));
-    lsum += e;
-    p[v] = (__bf16)e;
+  for (int v = 0; v < 16; v += 2) {
+    bf16x2 pr;
+    pr[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v], c, w.neg_mc));
+    pr[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v + 1], c, w.neg_mc));
+    p[v / 8][v % 8] = pr[0];
+    p[v / 8][v % 8 + 1] = pr[1];
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
   }
-  w.l += lsum;
+  return lsum;
 }
 
-// Causal / range-end mask of one 32-key score tile: element v is key
-// key0 + 8(v/4) + 4*half + v%4 and is visible iff it is below `lim`.
-__device__ __forceinline__ void mask_unit(f32x16& s, int key0, int lim, int half) {
-  int x = lim - key0 - 4 * half;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) s[v] = (8 * (v / 4) + (v % 4)) < x ? s[v] : -INFINITY;
+// SAFE mode: raise the reference to the maximum seen so far; returns the factor
+// alpha = 2^((m_old - m_new) c) for everything accumulated before (0 while
+// nothing was visible yet, 1 if the maximum did not move).
+__device__ __forceinline__ float raise_reference(WaveState& w, const f32x16& s, float c) {
+  float m_new = fmaxf(w.m, unit_max(s));
+  float mm = m_new == -INFINITY ? 0.f : m_new;
+  float alpha = __builtin_amdgcn_exp2f((w.m - mm) * c);
+  w.m = m_new;
+  w.neg_mc = mm * -c;
+  return alpha;
 }
 
 __device__ __forceinline__ void rescale(WaveState& w, float alpha) {
@@ -188,19 +206,29 @@ __device__ __forceinline__ void rescale(WaveState& w, float alpha) {
   }
 }
 
+// Causal / range-end mask of one 32-key score tile: element v is key
+// key0 + 8(v/4) + 4*half + v%4 and is visible iff it is below `lim`.
+__device__ __forceinline__ void mask_unit(f32x16& s, int key0, int lim, int half) {
+  int x = lim - key0 - 4 * half;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) s[v] = (8 * (v / 4) + (v % 4)) < x ? s[v] : -INFINITY;
+}
+
 // One pipeline stage holds three independent pieces of work:
 //   QK  : s_next  = K[unit u+1] Q^T          (8 MFMAs, K fragments from LDS at KOFF)
-//   SM  : p_cur   = softmax numerators of s_cur (unit u), updates w.m / w.l
+//   SM  : p_cur   = softmax numerators of s_cur (unit u), updates w.l / w.lmax
 //   PV  : O^T    += V[unit u-1]^T p_prev      (8 MFMAs, V^T fragments from LDS at VOFF)
 // so that the MFMAs of two units hide the exponentials of the third.  The
 // sched_group_barrier sequence at the end pins the instruction order inside the
 // stage: operand fragments are read from LDS two MFMA pairs ahead of their use
-// and about five VALU instructions sit between consecutive MFMAs.
-template <bool QK, bool SM, bool PV, int KOFF, int VOFF>
+// and a few VALU instructions sit between consecutive MFMAs.  Returns the
+// rescale factor for the accumulators (SAFE mode; 1 otherwise), to be applied
+// after the stage, i.e. after the PV MFMAs of unit u-1 and before those of u.
+template <bool SAFE, bool QK, bool SM, bool PV, int KOFF, int VOFF>
 __device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16& s_next,
                                        f32x16& s_cur, bf16x8 (&p_cur)[2],
                                        const bf16x8 (&p_prev)[2], float c) {
-  float alpha = 1.0f, neg_mc = 0.f;
+  float alpha = 1.0f;
   bf16x8 kf[8], vf[8];
   // Keep this stage's softmax inside the stage: without the anchors the optimizer
   // hoists it above the preceding barrier and sinks the row sums to the loop end.
@@ -219,9 +247,14 @@ __device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16&
     }
   }
   if (SM) {
-    softmax_head(w, s_cur, c, &alpha, &neg_mc);
-    softmax_half<0>(w, s_cur, p_cur[0], c, neg_mc);
-    softmax_half<1>(w, s_cur, p_cur[1], c, neg_mc);
+    if (SAFE) {
+      alpha = raise_reference(w, s_cur, c);
+      w.l = __builtin_fmaf(w.l, alpha, softmax_unit(w, s_cur, p_cur, c));
+    } else {
+      float lsum = softmax_unit(w, s_cur, p_cur, c);
+      w.l += lsum;
+      w.lmax = fmaxf(w.lmax, lsum);
+    }
   }
   if (QK) {
 #pragma unroll
@@ -237,13 +270,13 @@ __device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16&
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 3, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 4, 0);
     }
   }
-  if (SM) asm volatile("" : "+v"(w.l), "+v"(w.m), "+v"(p_cur[0]), "+v"(p_cur[1]));
+  if (SM) asm volatile("" : "+v"(w.l), "+v"(w.lmax), "+v"(p_cur[0]), "+v"(p_cur[1]));
   __builtin_amdgcn_sched_barrier(0);
   return alpha;
 }
@@ -255,7 +288,7 @@ __device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16&
 //   stage B: scores of unit 2t+3 | softmax of unit 2t+2 | PV of unit 2t+1.
 // MORE = tile t+1 exists.  KN / VC are the LDS offsets of K tile t+1 and V tile t,
 // KF / VF those of the buffers that are refilled (K tile t+2, V tile t+1).
-template <bool MORE, int KN, int VC, int KF, int VF>
+template <bool SAFE, bool MORE, int KN, int VC, int KF, int VF>
 __device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, const TileSeq& seq,
                                           const char* Kb, const char* Vb, int t, int row_lim,
                                           int wave_lo, float c, unsigned lds0, f32x16& sA,
@@ -273,24 +306,85 @@ __device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, cons
     seq.tile(t + 1, &nk0, &nhi);
     issue_tile(Vb, nk0, nhi, lds0 + VF, la);
     const int nlim = row_lim < nhi ? row_lim : nhi;
-    float alpha = stage<true, true, true, KN, VC>(w, la, sA, sB, pB, pA, c);
-    rescale(w, alpha);
+    float alpha = stage<SAFE, true, true, true, KN, VC>(w, la, sA, sB, pB, pA, c);
+    if (SAFE) rescale(w, alpha);
     if (nk0 + 32 > wave_lo || nk0 + 32 > nhi) mask_unit(sA, nk0, nlim, la.half);
-    alpha = stage<true, true, true, KN + H, VC + H>(w, la, sB, sA, pA, pB, c);
-    rescale(w, alpha);
+    alpha = stage<SAFE, true, true, true, KN + H, VC + H>(w, la, sB, sA, pA, pB, c);
+    if (SAFE) rescale(w, alpha);
     if (nk0 + 64 > wave_lo || nk0 + 64 > nhi) mask_unit(sB, nk0 + 32, nlim, la.half);
   } else {
-    float alpha = stage<false, true, true, 0, VC>(w, la, sA, sB, pB, pA, c);
-    rescale(w, alpha);
-    stage<false, false, true, 0, VC + H>(w, la, sB, sA, pA, pB, c);
+    float alpha = stage<SAFE, false, true, true, 0, VC>(w, la, sA, sB, pB, pA, c);
+    if (SAFE) rescale(w, alpha);
+    stage<SAFE, false, false, true, 0, VC + H>(w, la, sB, sA, pA, pB, c);
   }
 }
 
-// Walk a tile sequence for the calling wavefront (all four wavefronts of the
-// workgroup call this with the same sequence).
+// Walk a tile sequence once for the calling wavefront (all four wavefronts of
+// the workgroup call this with the same sequence).
 //   row_lim     this lane's exclusive causal key bound (0 for an inactive row)
 //   wave_lo     smallest row_lim among the wavefront's active rows: key tiles that
 //               end at or below it need no causal mask
+template <bool SAFE>
+__device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const TileSeq& seq,
+                                         const char* Kb, const char* Vb, int row_lim, int wave_lo,
+                                         float c, unsigned lds0) {
+  const int T = seq.n_tiles;
+  constexpr int K0 = LDS_K0, K1 = LDS_K1, V0 = LDS_V0, V1 = LDS_V1, H = 32 * ROWB;
+  f32x16 sA, sB;              // score tiles of the even / odd 32-key unit
+  bf16x8 pA[2], pB[2];        // their exponentials (bf16)
+  int key0, hi;
+
+  // Prologue: K tile 0, V tile 0 and K tile 1 in flight; scores of tile 0.
+  seq.tile(0, &key0, &hi);
+  issue_tile(Kb, key0, hi, lds0 + K0, la);
+  issue_tile(Vb, key0, hi, lds0 + V0, la);
+  if (T > 1) {
+    int k1, h1;
+    seq.tile(1, &k1, &h1);
+    issue_tile(Kb, k1, h1, lds0 + K1, la);
+    wait_vmcnt8();
+  } else {
+    wait_vmcnt0();
+  }
+  __builtin_amdgcn_s_barrier();
+  const int lim0 = row_lim < hi ? row_lim : hi;
+  stage<SAFE, true, false, false, K0, 0>(w, la, sA, sA, pA, pA, c);
+  if (key0 + 32 > wave_lo || key0 + 32 > hi) mask_unit(sA, key0, lim0, la.half);
+  stage<SAFE, true, false, false, K0 + H, 0>(w, la, sB, sA, pA, pA, c);
+  if (key0 + 64 > wave_lo || key0 + 64 > hi) mask_unit(sB, key0 + 32, lim0, la.half);
+  // first unit: its row maximum becomes the reference (nothing to rescale yet)
+  raise_reference(w, sA, c);
+  w.l = softmax_unit(w, sA, pA, c);
+
+  // Tile t: V tile t is consumed while K tile t+1 produces the next scores.
+  // The loop is unrolled by two so that every LDS buffer offset is an immediate
+  // and the accumulators flow through straight-line code.
+  int t = 0;
+  for (; t + 2 < T; t += 2) {
+    tile_step<SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+    tile_step<SAFE, true, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+  }
+  if (T - t == 2) {
+    tile_step<SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+    tile_step<SAFE, false, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+  } else {
+    tile_step<SAFE, false, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+  }
+}
+
+__device__ __forceinline__ void reset_state(WaveState& w) {
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) w.o[dt][v] = 0.f;
+  w.m = -INFINITY;
+  w.neg_mc = 0.f;
+  w.l = 0.f;
+  w.lmax = 0.f;
+}
+
+// Attention of the workgroup's rows over a tile sequence: the fast loop, and the
+// exact loop again if any wavefront's scores left the fast loop's safe range.
 __device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const char* Kb,
                                        const char* Vb, int row_lim, int wave_lo,
                                        float c, unsigned lds0) {
@@ -315,50 +409,28 @@ __device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const c
         la.v[dt][u] = lds0 + r * ROWB + ((chunk ^ swz(r)) << 4) + 8 * (lane & 1);
       }
     unsigned chunk_off = ((la.tid & 15) ^ swz(la.tid >> 4)) << 4;
+    la.dma = (la.tid >> 4) * ROWB + chunk_off;
+  }
+  if (seq.n_tiles == 0) return;
+  // Consume the Q fragments here so that the compiler places its own wait for
+  // their loads before the first DMA is in flight (and none inside the loops).
 #pragma unroll
-    for (int it = 0; it < 4; ++it) la.dma[it] = (it * 16 + (la.tid >> 4)) * ROWB + chunk_off;
-  }
-  const int T = seq.n_tiles;
-  if (T == 0) return;
-  wait_vmcnt0();              // Q fragments are in registers before any DMA is counted
+  for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(w.q[t]));
+  key_loop<false>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
 
-  constexpr int K0 = LDS_K0, K1 = LDS_K1, V0 = LDS_V0, V1 = LDS_V1, H = 32 * ROWB;
-  f32x16 sA, sB;              // score tiles of the even / odd 32-key unit
-  bf16x8 pA[2], pB[2];        // their exponentials (bf16)
-  int key0, hi;
-
-  // Prologue: K tile 0, V tile 0 and K tile 1 in flight; scores of tile 0.
-  seq.tile(0, &key0, &hi);
-  issue_tile(Kb, key0, hi, lds0 + K0, la);
-  issue_tile(Vb, key0, hi, lds0 + V0, la);
-  if (T > 1) {
-    int k1, h1;
-    seq.tile(1, &k1, &h1);
-    issue_tile(Kb, k1, h1, lds0 + K1, la);
-    wait_vmcnt8();
-  } else {
-    wait_vmcnt0();
-  }
-  __builtin_amdgcn_s_barrier();
-  const int lim0 = row_lim < hi ? row_lim : hi;
-  stage<true, false, false, K0, 0>(w, la, sA, sA, pA, pA, c);
-  if (key0 + 32 > wave_lo || key0 + 32 > hi) mask_unit(sA, key0, lim0, la.half);
-  stage<true, true, false, K0 + H, 0>(w, la, sB, sA, pA, pA, c);
-  if (key0 + 64 > wave_lo || key0 + 64 > hi) mask_unit(sB, key0 + 32, lim0, la.half);
-
-  // Tile t: V tile t is consumed while K tile t+1 produces the next scores.
-  // The loop is unrolled by two so that every LDS buffer offset is an immediate
-  // and the accumulators flow through straight-line code.
-  int t = 0;
-  for (; t + 2 < T; t += 2) {
-    tile_step<true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
-    tile_step<true, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
-  }
-  if (T - t == 2) {
-    tile_step<true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
-    tile_step<false, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
-  } else {
-    tile_step<false, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+  // Did any row of any wavefront leave the safe range?  One LDS word per
+  // wavefront; __syncthreads() (fence + barrier) orders the tile reads before the
+  // flag writes, the writes before the reads, and the reads before any new DMA.
+  __syncthreads();
+  const bool bad = __builtin_amdgcn_ballot_w64(!(w.lmax < LSUM_LIMIT)) != 0;
+  LDS_AS int* flags = (LDS_AS int*)(size_t)lds0;
+  if (lane == 0) flags[la.tid >> 6] = bad ? 1 : 0;
+  __syncthreads();
+  const int any_bad = flags[0] | flags[1] | flags[2] | flags[3];
+  __syncthreads();
+  if (__builtin_expect(any_bad != 0, 0)) {
+    reset_state(w);
+    key_loop<true>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
   }
 }
 
@@ -370,7 +442,9 @@ __device__ __forceinline__ void load_q(WaveState& w, const char* qrow, int half)
 #pragma unroll
     for (int v = 0; v < 16; ++v) w.o[dt][v] = 0.f;
   w.m = -INFINITY;
+  w.neg_mc = 0.f;
   w.l = 0.f;
+  w.lmax = 0.f;
 }
 
 // ------------------------------------------------------------------ phase 1

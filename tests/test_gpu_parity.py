@@ -52,6 +52,16 @@ def test_bf16_small_every_row(Hq, Hkv, L, b, a, lq, nd):
     _report(ph.run_parity(cfg, all_rows=True))
 
 
+def test_bf16_extreme_scores_take_the_exact_softmax_path():
+    """Planted rows with gamma = 6 put one logit ~65 nats above everything a row
+    saw in its first keys: the fast key loop's fixed reference maximum is no
+    longer safe and the workgroup must redo its rows with the exact online
+    softmax.  Rows without such a key share workgroups with rows that have one."""
+    cfg = workloads.StarConfig("bf16peaky", "bf16", 1, 8, 2, 128, 3072, 1024, 512, 96, 3,
+                               seed=77, n_planted=16, gamma=6.0)
+    _report(ph.run_parity(cfg, all_rows=True))
+
+
 def test_config2_bf16_sampled():
     _report(ph.run_parity(workloads.CONFIGS["C2"], verbose=True))
 
