@@ -41,18 +41,40 @@ static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
 // Heads of one KV group that share a workgroup in the bf16 row-tiled kernels.
 int heads_per_workgroup(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
 
-// Split plan for a phase-2 call with q_len new tokens.  Decode-sized calls
-// (G * q_len rows fit one 16-column MFMA tile) stream the cache with many short
-// splits so that every CU has loads in flight; larger calls are compute-bound
-// and use as few splits as still fill the GPU.
-static bool make_plan(const star_attn_shape* s, int64_t q_len, SplitPlan* p) {
+// Workgroups of the decode kernel that are resident at once on an MI355X:
+// 256 CUs x 3 (the kernel's 48 KiB LDS ring allows three per CU).
+constexpr int64_t DECODE_SLOTS = 256 * 3;
+
+// Split plan for a phase-2 call with q_len new tokens that can see `total`
+// cache rows.  Decode-sized calls (G * q_len rows fit one 16-column MFMA tile)
+// stream the cache: without per-part outputs the keys of each (batch, KV head)
+// are cut into equal splits, one per resident workgroup; with per-part outputs
+// the splits respect block boundaries.  Larger calls are compute-bound and use
+// as few splits as still fill the GPU.
+static bool make_plan(const star_attn_shape* s, int64_t q_len, int64_t total, bool want_parts,
+                      SplitPlan* p) {
   Geom g = make_geom(s);
   int64_t n = ceil_div(g.L, g.b);
   int64_t bmax = g.b < g.L ? g.b : g.L;
   int64_t tail_cap = g.cap - g.L;
   int64_t rows = (int64_t)g.G * q_len;
   p->decode = (s->dtype == STAR_ATTN_BF16 && rows <= 16) ? 1 : 0;
+  p->flat = 0;
+  p->n_blocks = (int32_t)n;
+  if (n > (1 << 24)) return false;
   int64_t split_len;
+  if (p->decode && !want_parts) {
+    int64_t pairs = (int64_t)g.B * g.Hkv;
+    int64_t s0 = DECODE_SLOTS / pairs > 1 ? DECODE_SLOTS / pairs : 1;
+    split_len = round_up(ceil_div(total, s0), 32);
+    if (split_len < 64) split_len = 64;
+    p->flat = 1;
+    p->split_len = split_len;
+    p->spb = 0;
+    p->st = 0;
+    p->s_total = (int32_t)ceil_div(total, split_len);
+    return true;
+  }
   if (p->decode) {
     int64_t key_heads = g.cap * g.B * g.Hkv;
     int64_t want = ceil_div(key_heads, 2048);
@@ -75,11 +97,10 @@ static bool make_plan(const star_attn_shape* s, int64_t q_len, SplitPlan* p) {
   int64_t spb = ceil_div(bmax, split_len);
   int64_t st = tail_cap > 0 ? ceil_div(tail_cap, split_len) : 1;
   int64_t s_total = n * spb + st;
-  if (s_total > (1 << 24) || n > (1 << 24)) return false;
+  if (s_total > (1 << 24)) return false;
   p->split_len = split_len;
   p->spb = (int32_t)spb;
   p->st = (int32_t)st;
-  p->n_blocks = (int32_t)n;
   p->s_total = (int32_t)s_total;
   return true;
 }
@@ -105,10 +126,18 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
   size_t best = 0;
   auto consider = [&](int64_t q) {
     if (q < 1 || q > max_q_len) return;
-    SplitPlan p;
-    if (!make_plan(shape, q, &p)) return;
-    size_t b = plan_bytes(shape, p, q);
-    if (b > best) best = b;
+    for (int parts = 0; parts < 2; ++parts) {
+      SplitPlan p;
+      // the number of splits never exceeds what the full cache needs
+      if (!make_plan(shape, q, shape->cache_capacity, parts != 0, &p)) continue;
+      if (p.flat) {   // a shorter cache may need one split more than the full one; bound it
+        int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
+        int64_t s0 = DECODE_SLOTS / pairs > 1 ? DECODE_SLOTS / pairs : 1;
+        if (p.s_total < s0) p.s_total = (int32_t)s0;
+      }
+      size_t b = plan_bytes(shape, p, q);
+      if (b > best) best = b;
+    }
   };
   for (int64_t q = 1; q <= max_q_len && q <= 64; ++q) consider(q);
   for (int64_t q = 64; q <= max_q_len; q += 32) { consider(q); consider(q + 1); }
@@ -152,21 +181,26 @@ int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_
       ((uintptr_t)workspace & 255u))
     return STAR_ATTN_ERR_MISALIGNED;
   SplitPlan plan;
-  if (!make_plan(shape, q_len, &plan)) return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (!make_plan(shape, q_len, cache_len + q_len, O_part != nullptr, &plan))
+    return STAR_ATTN_ERR_INVALID_SHAPE;
   if (workspace_bytes < plan_bytes(shape, plan, q_len)) return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
   Geom g = make_geom(shape);
   if ((int64_t)g.B * plan.s_total * ((q_len + 31) / 32) * g.Hq > (int64_t)0x7fffffff)
     return STAR_ATTN_ERR_INVALID_SHAPE;
   hipStream_t st = (hipStream_t)hip_stream;
 
-  // Algorithm 2: the new tokens' K/V join the cache before they attend.
-  if (launch_cache_write(g, shape->dtype, Kq, Vq, K_cache, V_cache, q_len, cache_len, st) != hipSuccess)
+  // Algorithm 2: the new tokens' K/V join the cache before they attend.  The
+  // streaming decode kernel appends them itself (it reads the new rows from
+  // Kq/Vq and writes them to the cache); the other paths use the cache writer.
+  const bool fused_append = shape->dtype == STAR_ATTN_BF16 && plan.decode;
+  if (!fused_append &&
+      launch_cache_write(g, shape->dtype, Kq, Vq, K_cache, V_cache, q_len, cache_len, st) != hipSuccess)
     return STAR_ATTN_ERR_LAUNCH_FAILED;
 
   size_t rows = (size_t)g.B * plan.s_total * g.Hq * (size_t)q_len;
   Phase2Args a;
   a.g = g; a.plan = plan; a.cache_len = cache_len; a.q_len = (int32_t)q_len;
-  a.Qq = Qq; a.Kc = K_cache; a.Vc = V_cache;
+  a.Qq = Qq; a.Kn = Kq; a.Vn = Vq; a.Kc = K_cache; a.Vc = V_cache;
   a.O_sub = (float*)workspace;
   a.LSE_sub = (float*)workspace + rows * g.d;
   hipError_t e;

@@ -1,21 +1,26 @@
 // bf16 split-KV partial attention for decode-sized phase-2 calls (head_dim 128,
-// G * q_len <= 16 rows per KV head): Eq. 1-2 evaluated per split of the cache.
+// G * q_len <= 16 rows per KV head): Eq. 1-2 evaluated per split of the cache,
+// with Algorithm 2's "append, then attend" fused in.
 //
 // A decode step reads every cached K and V byte exactly once and does 4-8 flops
 // per byte, so the kernel is built as an HBM stream:
 //   * one wavefront per workgroup, one split (a contiguous run of keys of one
-//     KV head) per workgroup; thousands of independent workgroups, no barriers;
+//     KV head) per workgroup, no barriers; the host sizes the splits so that
+//     every resident workgroup slot gets one equal split;
 //   * the wavefront DMAs 32-key steps of K and V (8 KiB each) straight into a
-//     two-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
+//     three-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
 //     bursts, no VGPRs held by data in flight -- and waits with partial vmcnt so
-//     the next step is always in flight while the current one is consumed;
+//     that two steps are in flight while one is consumed;
 //   * all G query heads of the KV group (and up to 16/G new tokens) form the 16
 //     columns of v_mfma_f32_16x16x32_bf16, so K and V are read once per KV head;
 //     S^T = K Q^T leaves each lane with keys of one query column, and the
 //     exponentiated tile is directly the B operand of O^T += V^T P^T, with V^T
 //     fragments from the LDS transposing read;
 //   * 16-byte chunks of a key row are rotated-XOR swizzled in LDS so both operand
-//     reads are conflict-free.
+//     reads are conflict-free;
+//   * rows at or beyond cache_len are the new tokens: they are read from the
+//     call's Kq/Vq and written to the cache by the workgroup whose split holds
+//     them, so no separate append kernel runs before a decode step.
 // Each workgroup writes its split's normalised output rows and their
 // log-sum-exp; the merge kernel folds the splits (Eq. 3-4).
 #include "star_internal.h"
@@ -28,12 +33,13 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr int D = 128;
 constexpr int ROWB = D * 2;
 constexpr int STEP = 32;                 // keys per pipeline step
 constexpr int STEPB = STEP * ROWB;       // 8 KiB of K (and of V) per step
-constexpr int LDS_K0 = 0, LDS_V0 = STEPB, LDS_K1 = 2 * STEPB, LDS_V1 = 3 * STEPB;
+constexpr int RING = 3;                  // steps in the LDS ring
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -42,9 +48,15 @@ constexpr float LN2 = 0.6931471805599453f;
 // chunk c of key row r sits in slot c ^ swz(r)
 __device__ __forceinline__ int swz(int r) { return ((r << 1) & 15) | ((r >> 3) & 1); }
 
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
+// 16-byte DMA global -> LDS (lane L lands at lds_base + 16 L), address = sbase + voff
+__device__ __forceinline__ void dma16(const char* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
+// same with a full per-lane 64-bit address
+__device__ __forceinline__ void dma16_flat(const char* ptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(gptr), "s"(lds_base) : "memory");
+               :: "v"(ptr), "s"(lds_base) : "memory");
 }
 
 __device__ __forceinline__ float xor16(float x) {
@@ -65,25 +77,52 @@ struct DecState {
   float m, l;
 };
 
-// DMA one 32-key step of K and V.  Instruction `it` moves rows 4it..4it+3; lane
-// L moves (row 4it + L/16, slot L%16).  Rows past `hi` re-read the last valid row.
-__device__ __forceinline__ void issue_step(const char* Kb, const char* Vb, int key0, int hi,
-                                           unsigned ldsK, unsigned ldsV, int lane,
-                                           const int (&coff)[4]) {
+// Where a split's rows come from: cache rows below `cache_len`, the call's new
+// tokens (token-major, `new_stride` bytes between tokens) from there on.
+struct Source {
+  const char* Kb;      // cache base of this (batch, kv head)
+  const char* Vb;
+  const char* Kn;      // new-token base of this (batch, kv head)
+  const char* Vn;
+  int cache_len;
+  int new_stride;
+};
+
+// DMA one 32-key step of K and V into ring slot `slot`.  Instruction `it` moves
+// rows 4it..4it+3; lane L moves (row 4it + L/16, slot L%16).  Rows at or past
+// `hi` re-read the last valid row (they are masked in the score tile).
+__device__ __forceinline__ void issue_step(const Source& src, int key0, int hi, unsigned lds_slot,
+                                           int lane, const unsigned (&voff)[4]) {
+  const unsigned ldsK = lds_slot, ldsV = lds_slot + STEPB;
+  if (key0 + STEP <= hi && key0 + STEP <= src.cache_len) {   // whole step from the cache
+    const char* kb = src.Kb + (size_t)key0 * ROWB;
+    const char* vb = src.Vb + (size_t)key0 * ROWB;
 #pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    int key = key0 + 4 * it + (lane >> 4);
-    key = key < hi ? key : hi - 1;
-    size_t off = (size_t)key * ROWB + coff[it & 3];
-    dma16(Kb + off, ldsK + it * 1024);
-    dma16(Vb + off, ldsV + it * 1024);
+    for (int it = 0; it < 8; ++it) {
+      dma16(kb + (it >> 2) * 16 * ROWB, voff[it & 3], ldsK + it * 1024);
+      dma16(vb + (it >> 2) * 16 * ROWB, voff[it & 3], ldsV + it * 1024);
+    }
+  } else {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      int key = key0 + 4 * it + (lane >> 4);
+      key = key < hi ? key : hi - 1;
+      unsigned coff = voff[it & 3] & 255;
+      size_t off = key < src.cache_len ? (size_t)key * ROWB
+                                       : (size_t)(key - src.cache_len) * src.new_stride;
+      const char* kp = (key < src.cache_len ? src.Kb : src.Kn) + off + coff;
+      const char* vp = (key < src.cache_len ? src.Vb : src.Vn) + off + coff;
+      dma16_flat(kp, ldsK + it * 1024);
+      dma16_flat(vp, ldsV + it * 1024);
+    }
   }
 }
 
-template <int KOFF, int VOFF>
+template <int SLOT>
 __device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr)[4],
                                              const unsigned (&vaddr)[8], int key0, int lim,
                                              bool masked, float c, int j4) {
+  constexpr int KOFF = SLOT * 2 * STEPB, VOFF = KOFF + STEPB;
   f32x4 s[2];
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
@@ -139,9 +178,17 @@ __device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr
   }
 }
 
+// Wait until at most `pending` of the most recently issued steps are in flight
+// (16 DMA instructions per step).
+__device__ __forceinline__ void wait_steps(int pending) {
+  if (pending >= 2) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+  else if (pending == 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // grid: x = split, y = kv head, z = batch; 64 threads
 __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
-  __shared__ __attribute__((aligned(1024))) char lds[4 * STEPB];
+  __shared__ __attribute__((aligned(1024))) char lds[RING * 2 * STEPB];
   const Geom& g = a.g;
   const int lane = threadIdx.x;
   const int qc = lane & 15, j4 = lane >> 4;
@@ -150,7 +197,8 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   const int j = qc / g.G, head = kvh * g.G + qc % g.G;
   const bool live = qc < R;
 
-  int total = (int)(a.cache_len + a.q_len);
+  const int cache_len = (int)a.cache_len;
+  const int total = cache_len + a.q_len;
   int64_t lo64, hi64;
   split_range(a.plan, g.L, g.b, total, sp, &lo64, &hi64);
   const int lo = (int)lo64, hi = (int)hi64;
@@ -158,6 +206,26 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   if (lo >= hi) {                              // empty split (short block, unused tail)
     if (live && j4 == 0) a.LSE_sub[r] = -INFINITY;
     return;
+  }
+
+  Source src;
+  src.Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
+  src.Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
+  src.Kn = (const char*)a.Kn + ((size_t)beta * a.q_len * g.Hkv + kvh) * ROWB;
+  src.Vn = (const char*)a.Vn + ((size_t)beta * a.q_len * g.Hkv + kvh) * ROWB;
+  src.cache_len = cache_len;
+  src.new_stride = g.Hkv * ROWB;
+
+  // Algorithm 2, append: the new tokens whose rows fall into this split join the
+  // cache (16 lanes move one 256-byte row of K and of V).
+  if (hi > cache_len) {
+    int first = lo > cache_len ? lo : cache_len;
+    for (int key = first + (lane >> 4); key < hi; key += 4) {
+      size_t so = (size_t)(key - cache_len) * src.new_stride + (lane & 15) * 16;
+      size_t dof = (size_t)key * ROWB + (lane & 15) * 16;
+      *(i32x4*)(const_cast<char*>(src.Kb) + dof) = *(const i32x4*)(src.Kn + so);
+      *(i32x4*)(const_cast<char*>(src.Vb) + dof) = *(const i32x4*)(src.Vn + so);
+    }
   }
 
   DecState w;
@@ -175,6 +243,9 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
     w.m = -INFINITY;
     w.l = 0.f;
   }
+  // everything this wave loaded or stored so far is complete before DMAs are counted
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
   const unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
   // K operand: lane (i = lane%16, j4) reads row i, chunk 4t + j4
   unsigned kaddr[4];
@@ -189,39 +260,40 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
     for (int dt = 0; dt < 8; ++dt)
       vaddr[dt] = lds0 + rr * ROWB + (((2 * dt + ((lane & 3) >> 1)) ^ swz(rr)) << 4) + 8 * (lane & 1);
   }
-  int coff[4];
+  // DMA lane offsets: row (4it + lane/16) of a 16-row group, swizzled chunk
+  unsigned voff[4];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) coff[it] = ((lane & 15) ^ swz(4 * it + (lane >> 4))) << 4;
+  for (int it = 0; it < 4; ++it)
+    voff[it] = (4 * it + (lane >> 4)) * ROWB + (((lane & 15) ^ swz(4 * it + (lane >> 4))) << 4);
 
-  const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
-  const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   const float c = g.scale * LOG2E;
-  // token j sees cache rows [0, cache_len + j]; only splits that reach past
-  // cache_len (the tail) or end inside a step need the masking path
-  const int row_lim = live ? (int)a.cache_len + j + 1 : 0;
+  // token j sees rows [0, cache_len + j]; keys below free_hi are visible to every
+  // live column, so only steps reaching past it take the masking path
+  const int row_lim = live ? cache_len + j + 1 : 0;
   const int lim = row_lim < hi ? row_lim : hi;
-  const int free_hi = (int)a.cache_len + 1 < hi ? (int)a.cache_len + 1 : hi;  // keys below are visible to every live row
+  const int free_hi = cache_len + 1 < hi ? cache_len + 1 : hi;
 
   const int nsteps = (hi - lo + STEP - 1) / STEP;
-  issue_step(Kb, Vb, lo, hi, lds0 + LDS_K0, lds0 + LDS_V0, lane, coff);
-  if (nsteps > 1) issue_step(Kb, Vb, lo + STEP, hi, lds0 + LDS_K1, lds0 + LDS_V1, lane, coff);
-  for (int s = 0; s < nsteps; s += 2) {
-    int key0 = lo + s * STEP;
-    if (s + 1 < nsteps) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    compute_step<LDS_K0, LDS_V0>(w, kaddr, vaddr, key0, lim, key0 + STEP > free_hi, c, j4);
-    if (s + 1 >= nsteps) break;
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // ring slot 0 fully read
-    if (s + 2 < nsteps) {
-      issue_step(Kb, Vb, key0 + 2 * STEP, hi, lds0 + LDS_K0, lds0 + LDS_V0, lane, coff);
-      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // ring slot of step s is s % RING; RING - 1 steps are in flight while one is consumed
+  issue_step(src, lo, hi, lds0, lane, voff);
+  if (nsteps > 1) issue_step(src, lo + STEP, hi, lds0 + 2 * STEPB, lane, voff);
+  for (int s = 0; s < nsteps; s += RING) {
+#pragma unroll
+    for (int u = 0; u < RING; ++u) {
+      const int cur = s + u;
+      if (cur >= nsteps) break;
+      const int key0 = lo + cur * STEP;
+      // the slot that held step cur-1 is free: every LDS read of it has returned
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (cur + 2 < nsteps)
+        issue_step(src, key0 + 2 * STEP, hi, lds0 + ((u + 2) % RING) * 2 * STEPB, lane, voff);
+      int later = nsteps - 1 - cur;
+      wait_steps(later < 2 ? later : 2);
+      const bool masked = key0 + STEP > free_hi;
+      if (u == 0) compute_step<0>(w, kaddr, vaddr, key0, lim, masked, c, j4);
+      else if (u == 1) compute_step<1>(w, kaddr, vaddr, key0, lim, masked, c, j4);
+      else compute_step<2>(w, kaddr, vaddr, key0, lim, masked, c, j4);
     }
-    compute_step<LDS_K1, LDS_V1>(w, kaddr, vaddr, key0 + STEP, lim, key0 + 2 * STEP > free_hi, c, j4);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // ring slot 1 fully read
-    if (s + 3 < nsteps)
-      issue_step(Kb, Vb, key0 + 3 * STEP, hi, lds0 + LDS_K1, lds0 + LDS_V1, lane, coff);
   }
 
   float l_tot = w.l + xor16(w.l);

@@ -7,15 +7,21 @@
 // out; the parts are then folded in index order with the online-softmax update
 //     lse' = logaddexp(lse, lse_m),  O' = exp(lse - lse') O + exp(lse_m - lse') A_m,
 // which is what Eq. 3-4 evaluate to.  An empty split or part has lse = -inf and
-// weight 0.  The order of the folds is fixed, so results are deterministic.
+// weight 0.  Under a flat split plan everything is one part.  The order of every
+// fold is fixed, so results are deterministic.
 //
-// One workgroup per (batch, head, row); thread t owns output element t.
-// Traffic is s_total * (d + 1) floats per row -- negligible next to the cache.
+// One workgroup of 256 threads per (batch, head, row): eight groups of 32 lanes
+// walk the splits of a part eight at a time (independent loads, so their
+// latencies overlap), each lane owning d/32 output elements; the eight partial
+// sums are combined through LDS.  Traffic is s_total * (d + 1) floats per row --
+// negligible next to the cache.
 #include "star_internal.h"
 
 namespace star {
 
 namespace {
+
+constexpr int GROUPS = 8;
 
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
   unsigned int u = __float_as_uint(f);
@@ -24,63 +30,115 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
   return (unsigned short)(u >> 16);
 }
 
-__global__ void merge_kernel(MergeArgs a) {
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+  constexpr int E = D / 32;                  // output elements per lane
+  __shared__ float red_max[GROUPS];
+  __shared__ float red_w[GROUPS];
+  __shared__ float red_acc[GROUPS][D];
   const Geom& g = a.g;
-  const int d = g.d;
-  int t = threadIdx.x;
+  const int tid = threadIdx.x, grp = tid >> 5, li = tid & 31;
   int64_t row = blockIdx.x;                 // (beta, h, j), j fastest
   int j = (int)(row % a.q_len);
   int h = (int)((row / a.q_len) % g.Hq);
   int beta = (int)(row / ((int64_t)a.q_len * g.Hq));
   const SplitPlan& p = a.plan;
-  int64_t sub_stride = (int64_t)g.Hq * a.q_len;                       // rows between splits
-  int64_t base = ((int64_t)beta * p.s_total * g.Hq + h) * a.q_len + j; // split 0
-  int n_parts = p.n_blocks + 1;
+  const int64_t sub_stride = (int64_t)g.Hq * a.q_len;                       // rows between splits
+  const int64_t base = ((int64_t)beta * p.s_total * g.Hq + h) * a.q_len + j; // split 0
+  const int n_parts = p.flat ? 1 : p.n_blocks + 1;
 
-  float m_g = -INFINITY, l_g = 0.f, acc_g = 0.f;
+  float m_g = -INFINITY, l_g = 0.f;
+  float acc_g[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) acc_g[e] = 0.f;
+
   for (int m = 0; m < n_parts; ++m) {
-    int s_lo = m < p.n_blocks ? m * p.spb : p.n_blocks * p.spb;
-    int s_hi = m < p.n_blocks ? s_lo + p.spb : p.s_total;
+    int s_lo, s_hi;
+    if (p.flat) { s_lo = 0; s_hi = p.s_total; }
+    else if (m < p.n_blocks) { s_lo = m * p.spb; s_hi = s_lo + p.spb; }
+    else { s_lo = p.n_blocks * p.spb; s_hi = p.s_total; }
+
+    // part maximum of the split LSEs
     float pm = -INFINITY;
-    for (int s = s_lo; s < s_hi; ++s) pm = fmaxf(pm, a.LSE_sub[base + s * sub_stride]);
-    float A_m = 0.f, lse_m = -INFINITY;
+    for (int s = s_lo + tid; s < s_hi; s += 256) pm = fmaxf(pm, a.LSE_sub[base + s * sub_stride]);
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) pm = fmaxf(pm, __shfl_xor(pm, off, 32));
+    __syncthreads();                         // previous part's reads of red_* are done
+    if (li == 0) red_max[grp] = pm;
+    __syncthreads();
+    pm = red_max[0];
+#pragma unroll
+    for (int k = 1; k < GROUPS; ++k) pm = fmaxf(pm, red_max[k]);
+
+    // weighted sum of the split outputs, eight splits in flight
+    float wsum = 0.f;
+    float acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0.f;
     if (pm > -INFINITY) {
-      float wsum = 0.f, acc = 0.f;
-      for (int s = s_lo; s < s_hi; ++s) {
+      for (int s = s_lo + grp; s < s_hi; s += GROUPS) {
         float ls = a.LSE_sub[base + s * sub_stride];
         if (ls == -INFINITY) continue;
         float w = expf(ls - pm);
         wsum += w;
-        acc = __builtin_fmaf(w, a.O_sub[(base + s * sub_stride) * d + t], acc);
+        const float* src = a.O_sub + (base + s * sub_stride) * D + li * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = __builtin_fmaf(w, src[e], acc[e]);
       }
-      A_m = acc / wsum;
-      lse_m = pm + logf(wsum);
     }
-    if (a.O_part) {
-      int64_t pr = (((int64_t)beta * n_parts + m) * g.Hq + h) * a.q_len + j;
-      a.O_part[pr * d + t] = A_m;
-      if (t == 0) a.LSE_part[pr] = lse_m;
-    }
-    if (lse_m > -INFINITY) {
-      float m_new = fmaxf(m_g, lse_m);
-      float sc_old = expf(m_g - m_new);     // 0 on the first non-empty part
-      float sc_new = expf(lse_m - m_new);
-      acc_g = acc_g * sc_old + sc_new * A_m;
-      l_g = l_g * sc_old + sc_new;
-      m_g = m_new;
+    if (li == 0) red_w[grp] = wsum;
+#pragma unroll
+    for (int e = 0; e < E; ++e) red_acc[grp][li * E + e] = acc[e];
+    __syncthreads();
+
+    if (grp == 0) {
+      float wtot = 0.f;
+#pragma unroll
+      for (int k = 0; k < GROUPS; ++k) wtot += red_w[k];
+      float A_m[E];
+      float lse_m = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < GROUPS; ++k) t += red_acc[k][li * E + e];
+        A_m[e] = wtot > 0.f ? t / wtot : 0.f;
+      }
+      if (wtot > 0.f) lse_m = pm + logf(wtot);
+      if (a.O_part) {
+        int64_t pr = (((int64_t)beta * n_parts + m) * g.Hq + h) * a.q_len + j;
+#pragma unroll
+        for (int e = 0; e < E; ++e) a.O_part[pr * D + li * E + e] = A_m[e];
+        if (li == 0) a.LSE_part[pr] = lse_m;
+      }
+      if (lse_m > -INFINITY) {
+        float m_new = fmaxf(m_g, lse_m);
+        float sc_old = expf(m_g - m_new);     // 0 on the first non-empty part
+        float sc_new = expf(lse_m - m_new);
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc_g[e] = acc_g[e] * sc_old + sc_new * A_m[e];
+        l_g = l_g * sc_old + sc_new;
+        m_g = m_new;
+      }
     }
   }
-  float out = l_g > 0.f ? acc_g / l_g : 0.f;
-  int64_t orow = ((int64_t)beta * a.q_len + j) * g.Hq + h;
-  if (a.out_bf16) ((unsigned short*)a.O)[orow * d + t] = f32_to_bf16_rne(out);
-  else ((float*)a.O)[orow * d + t] = out;
+  if (grp == 0) {
+    int64_t orow = ((int64_t)beta * a.q_len + j) * g.Hq + h;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      float out = l_g > 0.f ? acc_g[e] / l_g : 0.f;
+      if (a.out_bf16) ((unsigned short*)a.O)[orow * D + li * E + e] = f32_to_bf16_rne(out);
+      else ((float*)a.O)[orow * D + li * E + e] = out;
+    }
+  }
 }
 
 }  // namespace
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st) {
   int64_t rows = (int64_t)a.g.B * a.g.Hq * a.q_len;
-  merge_kernel<<<dim3((unsigned)rows), dim3((unsigned)a.g.d), 0, st>>>(a);
+  if (a.g.d == 64) merge_kernel<64><<<dim3((unsigned)rows), 256, 0, st>>>(a);
+  else merge_kernel<128><<<dim3((unsigned)rows), 256, 0, st>>>(a);
   return hipGetLastError();
 }
 

@@ -15,13 +15,19 @@ namespace star {
 // Split index s in [0, n_blocks * spb) is context block s / spb, piece s % spb;
 // indices from n_blocks * spb on are pieces of the tail.
 // ---------------------------------------------------------------------------
+//
+// A "flat" plan ignores part boundaries: split s is simply keys
+// [s * split_len, (s + 1) * split_len) of everything the call may see.  It is
+// used by decode-sized calls that do not ask for per-part outputs, where equal
+// splits (one per resident workgroup) matter more than part boundaries.
 struct SplitPlan {
-  int64_t split_len;   // keys per split (multiple of 64)
+  int64_t split_len;   // keys per split (multiple of 32)
   int32_t spb;         // splits per context block
   int32_t st;          // splits for the tail [L, cache_capacity)
   int32_t n_blocks;    // n = ceil(L / b)
-  int32_t s_total;     // n_blocks * spb + st
+  int32_t s_total;     // n_blocks * spb + st  (flat: number of splits)
   int32_t decode;      // 1: streaming split-KV kernel, 0: row-tiled kernel
+  int32_t flat;        // 1: splits ignore part boundaries
 };
 
 // Geometry every kernel needs.  Strides are in elements.
@@ -46,8 +52,10 @@ struct Phase2Args {
   int64_t cache_len;    // tokens cached before this call
   int32_t q_len;
   const void* Qq;       // [B, q_len, Hq, d]
-  const void* Kc;       // caches, new tokens already appended
-  const void* Vc;
+  const void* Kn;       // new tokens' K, V [B, q_len, Hkv, d]
+  const void* Vn;
+  void* Kc;             // caches; the new tokens are already appended unless the
+  void* Vc;             // kernel appends them itself (decode path)
   float* O_sub;         // [B, s_total, Hq, q_len, d]   per-split local attention
   float* LSE_sub;       // [B, s_total, Hq, q_len]      per-split log-sum-exp
 };
@@ -68,7 +76,12 @@ struct MergeArgs {
 __host__ __device__ inline void split_range(const SplitPlan& p, int64_t L, int64_t b,
                                             int64_t total_keys, int s, int64_t* lo, int64_t* hi) {
   int n_ctx = p.n_blocks * p.spb;
-  if (s < n_ctx) {
+  if (p.flat) {
+    int64_t x = (int64_t)s * p.split_len;
+    int64_t y = x + p.split_len;
+    *lo = x < total_keys ? x : total_keys;
+    *hi = y < total_keys ? y : total_keys;
+  } else if (s < n_ctx) {
     int64_t m = s / p.spb, piece = s % p.spb;
     int64_t blo = m * b, bhi = (m + 1) * b < L ? (m + 1) * b : L;
     int64_t x = blo + piece * p.split_len;
