@@ -42,8 +42,11 @@ static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
 int heads_per_workgroup(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
 
 // Workgroups of the decode kernel that are resident at once on an MI355X:
-// 256 CUs x 3 (the kernel's 48 KiB LDS ring allows three per CU).
-constexpr int64_t DECODE_SLOTS = 256 * 3;
+// 256 CUs x 2 (the kernel's 64 KiB LDS ring allows two per CU).
+#ifndef STAR_DECODE_WGS_PER_CU
+#define STAR_DECODE_WGS_PER_CU 2
+#endif
+constexpr int64_t DECODE_SLOTS = 256 * STAR_DECODE_WGS_PER_CU;
 
 // Split plan for a phase-2 call with q_len new tokens that can see `total`
 // cache rows.  Decode-sized calls (G * q_len rows fit one 16-column MFMA tile)

@@ -8,9 +8,9 @@
 //     KV head) per workgroup, no barriers; the host sizes the splits so that
 //     every resident workgroup slot gets one equal split;
 //   * the wavefront DMAs 32-key steps of K and V (8 KiB each) straight into a
-//     three-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
+//     four-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
 //     bursts, no VGPRs held by data in flight -- and waits with partial vmcnt so
-//     that two steps are in flight while one is consumed;
+//     that three steps (48 KiB) are in flight while one is consumed;
 //   * all G query heads of the KV group (and up to 16/G new tokens) form the 16
 //     columns of v_mfma_f32_16x16x32_bf16, so K and V are read once per KV head;
 //     S^T = K Q^T leaves each lane with keys of one query column, and the
@@ -39,7 +39,10 @@ constexpr int D = 128;
 constexpr int ROWB = D * 2;
 constexpr int STEP = 32;                 // keys per pipeline step
 constexpr int STEPB = STEP * ROWB;       // 8 KiB of K (and of V) per step
-constexpr int RING = 3;                  // steps in the LDS ring
+#ifndef STAR_DECODE_RING
+#define STAR_DECODE_RING 4
+#endif
+constexpr int RING = STAR_DECODE_RING;   // steps in the LDS ring
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -181,7 +184,8 @@ __device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr
 // Wait until at most `pending` of the most recently issued steps are in flight
 // (16 DMA instructions per step).
 __device__ __forceinline__ void wait_steps(int pending) {
-  if (pending >= 2) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+  if (pending >= 3) asm volatile("s_waitcnt vmcnt(48)" ::: "memory");
+  else if (pending == 2) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
   else if (pending == 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
   else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
@@ -274,9 +278,13 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   const int free_hi = cache_len + 1 < hi ? cache_len + 1 : hi;
 
   const int nsteps = (hi - lo + STEP - 1) / STEP;
-  // ring slot of step s is s % RING; RING - 1 steps are in flight while one is consumed
-  issue_step(src, lo, hi, lds0, lane, voff);
-  if (nsteps > 1) issue_step(src, lo + STEP, hi, lds0 + 2 * STEPB, lane, voff);
+  // ring slot of step s is s % RING; AHEAD = RING - 1 steps are in flight while
+  // one is consumed
+  constexpr int AHEAD = RING - 1;
+  static_assert(RING >= 2 && RING <= 4, "vmcnt holds at most 63 outstanding DMAs");
+#pragma unroll
+  for (int i = 0; i < AHEAD; ++i)
+    if (i < nsteps) issue_step(src, lo + i * STEP, hi, lds0 + i * 2 * STEPB, lane, voff);
   for (int s = 0; s < nsteps; s += RING) {
 #pragma unroll
     for (int u = 0; u < RING; ++u) {
@@ -285,14 +293,15 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
       const int key0 = lo + cur * STEP;
       // the slot that held step cur-1 is free: every LDS read of it has returned
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (cur + 2 < nsteps)
-        issue_step(src, key0 + 2 * STEP, hi, lds0 + ((u + 2) % RING) * 2 * STEPB, lane, voff);
+      if (cur + AHEAD < nsteps)
+        issue_step(src, key0 + AHEAD * STEP, hi, lds0 + ((u + AHEAD) % RING) * 2 * STEPB, lane, voff);
       int later = nsteps - 1 - cur;
-      wait_steps(later < 2 ? later : 2);
+      wait_steps(later < AHEAD ? later : AHEAD);
       const bool masked = key0 + STEP > free_hi;
       if (u == 0) compute_step<0>(w, kaddr, vaddr, key0, lim, masked, c, j4);
       else if (u == 1) compute_step<1>(w, kaddr, vaddr, key0, lim, masked, c, j4);
-      else compute_step<2>(w, kaddr, vaddr, key0, lim, masked, c, j4);
+      else if (u == 2) compute_step<2>(w, kaddr, vaddr, key0, lim, masked, c, j4);
+      else compute_step<3>(w, kaddr, vaddr, key0, lim, masked, c, j4);
     }
   }
 

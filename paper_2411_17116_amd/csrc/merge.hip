@@ -11,9 +11,9 @@
 // fold is fixed, so results are deterministic.
 //
 // One workgroup of 256 threads per (batch, head, row): eight groups of 32 lanes
-// walk the splits of a part eight at a time (independent loads, so their
-// latencies overlap), each lane owning d/32 output elements; the eight partial
-// sums are combined through LDS.  Traffic is s_total * (d + 1) floats per row --
+// walk the splits of a part, each lane owning d/32 output elements and each
+// group folding its splits with a running maximum (loads of four splits are in
+// flight per group); the eight partial results are combined through LDS.  Traffic is s_total * (d + 1) floats per row --
 // negligible next to the cache.
 #include "star_internal.h"
 
@@ -58,38 +58,52 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     else if (m < p.n_blocks) { s_lo = m * p.spb; s_hi = s_lo + p.spb; }
     else { s_lo = p.n_blocks * p.spb; s_hi = p.s_total; }
 
-    // part maximum of the split LSEs
-    float pm = -INFINITY;
-    for (int s = s_lo + tid; s < s_hi; s += 256) pm = fmaxf(pm, a.LSE_sub[base + s * sub_stride]);
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) pm = fmaxf(pm, __shfl_xor(pm, off, 32));
-    __syncthreads();                         // previous part's reads of red_* are done
-    if (li == 0) red_max[grp] = pm;
-    __syncthreads();
-    pm = red_max[0];
-#pragma unroll
-    for (int k = 1; k < GROUPS; ++k) pm = fmaxf(pm, red_max[k]);
-
-    // weighted sum of the split outputs, eight splits in flight
-    float wsum = 0.f;
+    // Each group folds its splits (s_lo + grp, + 8, ...) with a running maximum;
+    // LSE and output loads of a split are independent of the fold, so several
+    // splits are in flight at once.
+    float pm = -INFINITY, wsum = 0.f;
     float acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = 0.f;
-    if (pm > -INFINITY) {
-      for (int s = s_lo + grp; s < s_hi; s += GROUPS) {
-        float ls = a.LSE_sub[base + s * sub_stride];
-        if (ls == -INFINITY) continue;
-        float w = expf(ls - pm);
-        wsum += w;
-        const float* src = a.O_sub + (base + s * sub_stride) * D + li * E;
+    for (int s0 = s_lo + grp; s0 < s_hi; s0 += 4 * GROUPS) {
+      float ls[4];
+      float v[4][E];
 #pragma unroll
-        for (int e = 0; e < E; ++e) acc[e] = __builtin_fmaf(w, src[e], acc[e]);
+      for (int u = 0; u < 4; ++u) {
+        int s = s0 + u * GROUPS;
+        ls[u] = -INFINITY;
+        if (s < s_hi) {
+          ls[u] = a.LSE_sub[base + s * sub_stride];
+          const float* src = a.O_sub + (base + s * sub_stride) * D + li * E;
+#pragma unroll
+          for (int e = 0; e < E; ++e) v[u][e] = src[e];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (ls[u] == -INFINITY) continue;        // empty split: weight 0, output unset
+        float m_new = fmaxf(pm, ls[u]);
+        float sc_old = expf(pm - m_new);         // 0 for the first non-empty split
+        float w = expf(ls[u] - m_new);
+        wsum = wsum * sc_old + w;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = acc[e] * sc_old + w * v[u][e];
+        pm = m_new;
       }
     }
-    if (li == 0) red_w[grp] = wsum;
-#pragma unroll
-    for (int e = 0; e < E; ++e) red_acc[grp][li * E + e] = acc[e];
+    // combine the eight groups: bring every group to the common maximum
+    __syncthreads();                         // previous part's reads of red_* are done
+    if (li == 0) red_max[grp] = pm;
     __syncthreads();
+    float pmax = red_max[0];
+#pragma unroll
+    for (int k = 1; k < GROUPS; ++k) pmax = fmaxf(pmax, red_max[k]);
+    float adj = pm > -INFINITY ? expf(pm - pmax) : 0.f;
+    if (li == 0) red_w[grp] = wsum * adj;
+#pragma unroll
+    for (int e = 0; e < E; ++e) red_acc[grp][li * E + e] = acc[e] * adj;
+    __syncthreads();
+    pm = pmax;
 
     if (grp == 0) {
       float wtot = 0.f;
