@@ -146,6 +146,17 @@ def cpu_baseline(cfg, inp, budget_s=12.0):
     }
 
 
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summaries
+    (profiles/traffic.json), or None if that kernel/workload was not profiled."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +165,9 @@ def main():
     ap.add_argument("--config", default="C3", choices=sorted(workloads.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-causal", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="profiling aid: also run one device copy of the K cache (known size) "
+                         "so that HBM byte counters can be scaled")
     ap.add_argument("--sections", default="phase1,query,decode",
                     help="profiling aid: comma list of phase1,query,decode to run")
     args = ap.parse_args()
@@ -180,6 +194,12 @@ def main():
         "Od": [torch.empty_like(inp.Qd[:, :1]) for _ in range(cfg.nd)],
     }
     sections = tuple(args.sections.split(","))
+    if args.calib_copy:
+        calib = torch.empty_like(Kc)
+        calib.copy_(Kc)
+        torch.cuda.synchronize()
+        print(f"calibration copy: {Kc.numel() * Kc.element_size()} bytes read and as many written",
+              file=sys.stderr)
     timer = Timer()
     for _ in range(args.warmup):
         run_step(cfg, shape, inp, bufs, timer, sections)
@@ -223,12 +243,13 @@ def main():
                    "query_encode_tflops": q_flops / (q_ms * 1e-3) / 1e12},
         "roofline": {"bound": "mfma", "kernel": "phase1_bf16_kernel" if cfg.dtype == "bf16" else "phase1_f32_kernel",
                      "achieved": p1_tflops, "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
-                     "unit": "TFLOP/s", "frac": p1_tflops / MFMA_PEAK_TFLOPS[cfg.dtype], "traffic": None,
+                     "unit": "TFLOP/s", "frac": p1_tflops / MFMA_PEAK_TFLOPS[cfg.dtype],
+                     "traffic": measured_traffic("phase1", cfg.name),
                      "note": "flops = 4 d per visible (query, key) pair; time = phase-1 call "
                              "(KV-cache write + attention kernel)"},
         "roofline_decode": {"bound": "hbm", "kernel": "decode_bf16_kernel" if cfg.dtype == "bf16" else "phase2_f32_kernel",
                             "achieved": dec_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": dec_gbs / HBM_PEAK_GBS, "traffic": None,
+                            "frac": dec_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("decode", cfg.name),
                             "note": "bytes = K and V of every cached token once; time = whole "
                                     "decode call (append + split-KV + merge)"},
         "wall_ms_per_step": wall_ms / args.steps,

@@ -1,0 +1,151 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and rejects bad arguments before enqueueing
+anything (every error path returns its documented code)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_17116_amd as sa
+from paper_2411_17116_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "star_attn.h")
+
+# status codes as the header defines them
+ERR = dict(INVALID_SHAPE=-1, NULL_POINTER=-2, UNSUPPORTED_HEAD_DIM=-3, UNSUPPORTED_DTYPE=-4,
+           ANCHOR_GT_BLOCK=-5, CACHE_OVERFLOW=-6, WORKSPACE_TOO_SMALL=-7, LAUNCH_FAILED=-8,
+           MISALIGNED=-9)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sa.lib_path()):
+        from paper_2411_17116_amd import build
+        build.build(verbose=False)
+    return sa.load_library()
+
+
+def good_shape(**kw):
+    base = dict(dtype="bf16", batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, ctx_len=1024,
+                block=256, anchor=256, cache_capacity=1024 + 64)
+    base.update(kw)
+    return sa.StarShape.make(**base)
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(star_attn_[a-z0-9_]+)\s*\(", text)
+    assert set(names) >= {"star_attn_phase1", "star_attn_phase2", "star_attn_workspace_bytes",
+                          "star_attn_status_string", "star_attn_kernel_path"}
+    for n in set(names):
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def test_header_status_codes_match(lib):
+    text = open(HEADER).read()
+    for name, code in ERR.items():
+        m = re.search(rf"STAR_ATTN_ERR_{name}\s*=\s*(-?\d+)", text)
+        assert m and int(m.group(1)) == code
+        assert sa.status_string(code) != "unknown status"
+    assert sa.status_string(0) == "ok"
+    assert sa.status_string(-1234) == "unknown status"
+
+
+def test_shape_struct_layout_matches_header():
+    # 6 x int32, 4 x int64, 2 x float = 24 + 32 + 8 bytes, no padding surprises
+    assert ctypes.sizeof(binding.StarShape) == 64
+    assert binding.StarShape.ctx_len.offset == 24
+    assert binding.StarShape.softmax_scale.offset == 56
+
+
+# Placeholder pointers: aligned, non-NULL, never dereferenced because every call
+# below is rejected by the host-side validation.
+def _p1(lib, shape, Q=0x1000, K=0x1000, V=0x1000, O=0x1000, LSE=None, Kc=0x1000, Vc=0x1000):
+    return lib.star_attn_phase1(ctypes.byref(shape) if shape is not None else None,
+                                Q, K, V, O, LSE, Kc, Vc, None, 0, None)
+
+
+def _p2(lib, shape, cache_len, q_len, Qq=0x1000, Kq=0x1000, Vq=0x1000, Kc=0x1000, Vc=0x1000,
+        Op=None, Lp=None, O=0x1000, ws=0x1000, ws_bytes=1 << 40):
+    return lib.star_attn_phase2(ctypes.byref(shape), cache_len, q_len, Qq, Kq, Vq, Kc, Vc, Op, Lp,
+                                O, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dtype=7), "UNSUPPORTED_DTYPE"),
+    (dict(batch=0), "INVALID_SHAPE"),
+    (dict(n_q_heads=6, n_kv_heads=4), "INVALID_SHAPE"),
+    (dict(ctx_len=0), "INVALID_SHAPE"),
+    (dict(block=0), "INVALID_SHAPE"),
+    (dict(head_dim=96), "UNSUPPORTED_HEAD_DIM"),
+    (dict(head_dim=64), "UNSUPPORTED_HEAD_DIM"),          # bf16 path is d = 128 only
+    (dict(dtype="fp32", head_dim=32), "UNSUPPORTED_HEAD_DIM"),
+    (dict(anchor=257), "ANCHOR_GT_BLOCK"),
+    (dict(anchor=-1), "ANCHOR_GT_BLOCK"),
+    (dict(cache_capacity=1000), "CACHE_OVERFLOW"),
+    (dict(softmax_scale=-1.0), "INVALID_SHAPE"),
+])
+def test_bad_shapes_are_rejected_by_both_entry_points(lib, kw, code):
+    shape = good_shape(**kw)
+    assert _p1(lib, shape) == ERR[code]
+    assert _p2(lib, shape, shape.ctx_len, 1) == ERR[code]
+    assert sa.workspace_bytes(shape, 8) == 0
+    assert sa.kernel_path(shape) is None
+
+
+def test_null_and_misaligned_pointers(lib):
+    shape = good_shape()
+    assert _p1(lib, None) == ERR["NULL_POINTER"]
+    for arg in ("Q", "K", "V", "O", "Kc", "Vc"):
+        assert _p1(lib, shape, **{arg: None}) == ERR["NULL_POINTER"]
+        assert _p1(lib, shape, **{arg: 0x1008}) == ERR["MISALIGNED"]
+    L = shape.ctx_len
+    for arg in ("Qq", "Kq", "Vq", "Kc", "Vc", "O", "ws"):
+        assert _p2(lib, shape, L, 1, **{arg: None}) == ERR["NULL_POINTER"]
+    assert _p2(lib, shape, L, 1, Op=0x1000, Lp=None) == ERR["NULL_POINTER"]   # parts come in pairs
+    assert _p2(lib, shape, L, 1, Op=None, Lp=0x1000) == ERR["NULL_POINTER"]
+    assert _p2(lib, shape, L, 1, Qq=0x1004) == ERR["MISALIGNED"]
+    assert _p2(lib, shape, L, 1, ws=0x1010) == ERR["MISALIGNED"]             # workspace: 256 bytes
+
+
+def test_phase2_call_arguments(lib):
+    shape = good_shape()
+    L, cap = shape.ctx_len, shape.cache_capacity
+    assert _p2(lib, shape, L, 0) == ERR["INVALID_SHAPE"]
+    assert _p2(lib, shape, L - 1, 1) == ERR["INVALID_SHAPE"]          # cache_len below the context
+    assert _p2(lib, shape, cap, 1) == ERR["CACHE_OVERFLOW"]
+    assert _p2(lib, shape, cap - 3, 4) == ERR["CACHE_OVERFLOW"]
+    need = sa.workspace_bytes(shape, 16)
+    assert need > 0 and need % 256 == 0
+    # (every call in this file carries at least one invalid argument, so nothing
+    # is ever enqueued with the placeholder pointers)
+    assert _p2(lib, shape, L, 16, ws_bytes=64) == ERR["WORKSPACE_TOO_SMALL"]
+    assert _p2(lib, shape, L, 1, ws_bytes=64) == ERR["WORKSPACE_TOO_SMALL"]
+    assert _p2(lib, shape, L, 16, Op=0x1000, Lp=0x1000, ws_bytes=64) == ERR["WORKSPACE_TOO_SMALL"]
+
+
+def test_workspace_query_covers_every_call_size(lib):
+    """The size reported for max_q_len covers every smaller call: it never
+    shrinks as max_q_len grows."""
+    for shape in (good_shape(), good_shape(dtype="fp32", head_dim=64, n_q_heads=1, n_kv_heads=1),
+                  good_shape(ctx_len=100000, block=8192, anchor=2048, cache_capacity=100500,
+                             n_q_heads=64, n_kv_heads=8, batch=2)):
+        sizes = [sa.workspace_bytes(shape, q) for q in (1, 2, 3, 4, 5, 16, 17, 64, 65, 200, 256)]
+        assert all(s > 0 for s in sizes)
+        assert sizes == sorted(sizes), "requirement must not shrink as max_q_len grows"
+
+
+def test_kernel_path_names(lib):
+    assert sa.kernel_path(good_shape()) == "bf16-mfma"
+    assert sa.kernel_path(good_shape(dtype="fp32", head_dim=64)) == "f32-valu"
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    """No CPU fallback: a missing library is an error, not a silent slow path."""
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(FileNotFoundError):
+        binding.load_library()
