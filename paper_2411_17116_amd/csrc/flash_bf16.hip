@@ -36,7 +36,7 @@
 
 namespace star {
 
-int heads_per_workgroup(int G);   // defined with the split plan
+int heads_per_workgroup(int G, int row_blocks);   // defined with the split plan
 
 namespace {
 
@@ -52,6 +52,16 @@ constexpr int TKEYS = 64;                  // keys per LDS tile
 constexpr int ROWB = D * 2;                // bytes per key row
 constexpr int TILEB = TKEYS * ROWB;        // 16 KiB
 constexpr int LDS_K0 = 0, LDS_K1 = TILEB, LDS_V0 = 2 * TILEB, LDS_V1 = 3 * TILEB;
+// Wavefronts per workgroup.  All of them walk the same K/V tiles, so the L2 -> LDS
+// traffic per flop falls with NW; 8 wavefronts of <= 256 registers are two per SIMD.
+#ifndef STAR_FLASH_WAVES
+#define STAR_FLASH_WAVES 8
+#endif
+constexpr int NW = STAR_FLASH_WAVES;
+constexpr int NT = 64 * NW;                // threads per workgroup
+constexpr int DMA_ROWS = NT / 16;          // key rows one DMA instruction of the workgroup moves
+constexpr int DMA_ITERS = TKEYS / DMA_ROWS;
+static_assert(NW == 4 || NW == 8, "tile DMA is written for 4 or 8 wavefronts");
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -90,7 +100,11 @@ __device__ __forceinline__ float pair_sum(float x) {
 // Waits for the DMAs.  They must be opaque asm: the DMAs themselves are opaque
 // to the compiler, which would drop a builtin s_waitcnt it believes redundant.
 __device__ __forceinline__ void wait_vmcnt0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-__device__ __forceinline__ void wait_vmcnt8() { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
+// all but the two most recent tile DMAs (DMA_ITERS instructions each) have landed
+__device__ __forceinline__ void wait_vmcnt_2tiles() {
+  if (DMA_ITERS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+}
 
 // Sequence of key tiles a workgroup walks: first the tiles of [0, a_hi)
 // (n_a of them), then the tiles of [loc_lo, loc_hi).
@@ -106,12 +120,16 @@ struct TileSeq {
   }
 };
 
+// RB = row blocks of 32 query rows per wavefront.  Every K / V^T fragment read
+// from LDS feeds RB MFMAs, so RB = 2 halves the LDS traffic per flop (with RB = 1
+// the 4 SIMDs of a CU ask LDS for ~1 KiB per MFMA, which is its whole bandwidth).
+template <int RB>
 struct WaveState {
-  bf16x8 q[8];        // Q^T fragments: q[t] = Q[row lane%32][16t + 8*(lane/32) .. +7]
-  f32x16 o[4];        // O^T accumulators: o[dt][v] = O[row][32dt + 8(v/4) + 4(lane/32) + v%4]
-  float m;            // reference maximum of the raw logits (pair-uniform); see softmax_fix
-  float neg_mc;       // -m * c (0 while m == -inf)
-  float l;            // this lane's share of the running sum of 2^((s-m) c)
+  bf16x8 q[RB][8];    // Q^T fragments: q[rb][t] = Q[row lane%32 of block rb][16t + 8*(lane/32) .. +7]
+  f32x16 o[RB][4];    // O^T accumulators: o[rb][dt][v] = O[row][32dt + 8(v/4) + 4(lane/32) + v%4]
+  float m[RB];        // reference maximum of the raw logits (pair-uniform)
+  float neg_mc[RB];   // -m * c (0 while m == -inf)
+  float l[RB];        // this lane's share of the running sum of 2^((s-m) c)
   float lmax;         // largest per-unit partial row sum seen by the fast loop
 };
 
@@ -125,7 +143,7 @@ struct LaneAddr {
 };
 
 // Issue the DMA of one 64-key tile of K or V into an LDS tile buffer.  Thread
-// `tid` moves the 16-byte unit (row it*16 + tid/16, slot tid%16) for it = 0..3;
+// `tid` moves the 16-byte unit (row it*DMA_ROWS + tid/16, slot tid%16) for each it;
 // rows at or past `hi` re-read the last valid row (they are masked in the score
 // tile, and finite values keep 0 * V finite).
 __device__ __forceinline__ void issue_tile(const char* base, int key0, int hi, unsigned lds,
@@ -134,14 +152,15 @@ __device__ __forceinline__ void issue_tile(const char* base, int key0, int hi, u
   if (key0 + TKEYS <= hi) {            // full tile: scalar base, constant lane offsets
     const char* sb = base + (size_t)key0 * ROWB;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) dma16(sb + it * 16 * ROWB, la.dma, lds + it * 4096 + wave_base);
+    for (int it = 0; it < DMA_ITERS; ++it)
+      dma16(sb + it * DMA_ROWS * ROWB, la.dma, lds + it * DMA_ROWS * ROWB + wave_base);
   } else {
     int chunk_off = la.dma & 255;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      int key = key0 + it * 16 + (la.tid >> 4);
+    for (int it = 0; it < DMA_ITERS; ++it) {
+      int key = key0 + it * DMA_ROWS + (la.tid >> 4);
       key = key < hi ? key : hi - 1;
-      dma16(base, (unsigned)key * ROWB + chunk_off, lds + it * 4096 + wave_base);
+      dma16(base, (unsigned)key * ROWB + chunk_off, lds + it * DMA_ROWS * ROWB + wave_base);
     }
   }
 }
@@ -165,19 +184,18 @@ __device__ __forceinline__ float unit_max(const f32x16& s) {
   return pair_max(fmaxf(fmaxf(fmaxf(t0, t1), fmaxf(t2, t3)), fmaxf(t4, s[15])));
 }
 
-// Softmax numerators of one 32-key score tile against the reference w.m:
+// Softmax numerators of one 32-key score tile against a reference maximum:
 // p = 2^(s c - m c) rounded to bf16, and the lane's sum of the ROUNDED values
 // (v_dot2 with a vector of ones), so numerator and denominator see the same
 // rounding.
-__device__ __forceinline__ float softmax_unit(const WaveState& w, const f32x16& s, bf16x8 (&p)[2],
-                                              float c) {
+__device__ __forceinline__ float softmax_unit(const f32x16& s, float neg_mc, bf16x8 (&p)[2], float c) {
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   float lsum = 0.f;
 #pragma unroll
   for (int v = 0; v < 16; v += 2) {
     bf16x2 pr;
-    pr[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v], c, w.neg_mc));
-    pr[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v + 1], c, w.neg_mc));
+    pr[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v], c, neg_mc));
+    pr[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v + 1], c, neg_mc));
     p[v / 8][v % 8] = pr[0];
     p[v / 8][v % 8 + 1] = pr[1];
     lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
@@ -185,24 +203,31 @@ __device__ __forceinline__ float softmax_unit(const WaveState& w, const f32x16& 
   return lsum;
 }
 
-// SAFE mode: raise the reference to the maximum seen so far; returns the factor
-// alpha = 2^((m_old - m_new) c) for everything accumulated before (0 while
+// Raise the reference of row block rb to the maximum seen so far; returns the
+// factor alpha = 2^((m_old - m_new) c) for everything accumulated before (0 while
 // nothing was visible yet, 1 if the maximum did not move).
-__device__ __forceinline__ float raise_reference(WaveState& w, const f32x16& s, float c) {
-  float m_new = fmaxf(w.m, unit_max(s));
+template <int RB>
+__device__ __forceinline__ float raise_reference(WaveState<RB>& w, int rb, const f32x16& s, float c) {
+  float m_new = fmaxf(w.m[rb], unit_max(s));
   float mm = m_new == -INFINITY ? 0.f : m_new;
-  float alpha = __builtin_amdgcn_exp2f((w.m - mm) * c);
-  w.m = m_new;
-  w.neg_mc = mm * -c;
+  float alpha = __builtin_amdgcn_exp2f((w.m[rb] - mm) * c);
+  w.m[rb] = m_new;
+  w.neg_mc[rb] = mm * -c;
   return alpha;
 }
 
-__device__ __forceinline__ void rescale(WaveState& w, float alpha) {
-  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // some row maximum moved
+template <int RB>
+__device__ __forceinline__ void rescale(WaveState<RB>& w, const float (&alpha)[RB]) {
+  bool moved = false;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+  for (int rb = 0; rb < RB; ++rb) moved |= alpha[rb] != 1.0f;
+  if (__builtin_amdgcn_ballot_w64(moved) != 0) {   // some row maximum moved
 #pragma unroll
-      for (int v = 0; v < 16; ++v) w.o[dt][v] *= alpha;
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w.o[rb][dt][v] *= alpha[rb];
   }
 }
 
@@ -214,30 +239,59 @@ __device__ __forceinline__ void mask_unit(f32x16& s, int key0, int lim, int half
   for (int v = 0; v < 16; ++v) s[v] = (8 * (v / 4) + (v % 4)) < x ? s[v] : -INFINITY;
 }
 
+// Mask the score tiles of a unit [key0, key0 + 32) where some row of the
+// wavefront cannot see all of it (wave_lo = smallest causal bound in the wave).
+template <int RB>
+__device__ __forceinline__ void mask_if_needed(f32x16 (&s)[RB], int key0, int hi, int wave_lo,
+                                               const int (&row_lim)[RB], int half) {
+  if (key0 + 32 > wave_lo || key0 + 32 > hi) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) mask_unit(s[rb], key0, row_lim[rb] < hi ? row_lim[rb] : hi, half);
+  }
+}
+
 // One pipeline stage holds three independent pieces of work:
-//   QK  : s_next  = K[unit u+1] Q^T          (8 MFMAs, K fragments from LDS at KOFF)
+//   QK  : s_next  = K[unit u+1] Q^T          (8 RB MFMAs, K fragments from LDS at KOFF)
 //   SM  : p_cur   = softmax numerators of s_cur (unit u), updates w.l / w.lmax
-//   PV  : O^T    += V[unit u-1]^T p_prev      (8 MFMAs, V^T fragments from LDS at VOFF)
+//   PV  : O^T    += V[unit u-1]^T p_prev      (8 RB MFMAs, V^T fragments from LDS at VOFF)
 // so that the MFMAs of two units hide the exponentials of the third.  The
 // sched_group_barrier sequence at the end pins the instruction order inside the
-// stage: operand fragments are read from LDS two MFMA pairs ahead of their use
-// and a few VALU instructions sit between consecutive MFMAs.  Returns the
-// rescale factor for the accumulators (SAFE mode; 1 otherwise), to be applied
-// after the stage, i.e. after the PV MFMAs of unit u-1 and before those of u.
-template <bool SAFE, bool QK, bool SM, bool PV, int KOFF, int VOFF>
-__device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16& s_next,
-                                       f32x16& s_cur, bf16x8 (&p_cur)[2],
-                                       const bf16x8 (&p_prev)[2], float c) {
-  float alpha = 1.0f;
+// stage: operand fragments are read from LDS two fragment pairs ahead of their
+// use and a few VALU instructions sit between consecutive MFMAs.  `alpha`
+// receives the rescale factors for the accumulators (SAFE mode; 1 otherwise), to
+// be applied after the stage, i.e. after the PV MFMAs of unit u-1 and before
+// those of unit u.
+// PRE_IN: the first two K and V^T fragments were already read by the previous
+// stage and arrive in `pre`; PRE_OUT: this stage reads the first two fragment
+// pairs of the next stage (LDS offsets NKOFF / NVOFF) into `pre` behind its last
+// MFMAs, so that the next stage starts without waiting for LDS.
+struct PreFrag {
+  bf16x8 k[2], v[2];
+};
+
+template <int RB, bool SAFE, bool QK, bool SM, bool PV, int KOFF, int VOFF, bool PRE_IN = false,
+          bool PRE_OUT = false, int NKOFF = 0, int NVOFF = 0>
+__device__ __forceinline__ void stage(WaveState<RB>& w, const LaneAddr& la, f32x16 (&s_next)[RB],
+                                      f32x16 (&s_cur)[RB], bf16x8 (&p_cur)[RB][2],
+                                      const bf16x8 (&p_prev)[RB][2], float c, float (&alpha)[RB],
+                                      PreFrag& pre) {
   bf16x8 kf[8], vf[8];
   // Keep this stage's softmax inside the stage: without the anchors the optimizer
   // hoists it above the preceding barrier and sinks the row sums to the loop end.
-  if (SM) asm volatile("" : "+v"(s_cur));
+  if (SM) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(s_cur[rb]));
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
+    if (PRE_IN && i < 2) {
+      kf[i] = pre.k[i];
+      vf[i] = pre.v[i];
+      continue;
+    }
     if (QK) kf[i] = lds_read_b128(la.k[i] + KOFF);
     if (PV) {
-      // B operand p_prev[hf]: slot e of lane half h is key 16hf + 8(e/4) + 4h + e%4,
+      // B operand p_prev[.][hf]: slot e of lane half h is key 16hf + 8(e/4) + 4h + e%4,
       // so the A operand needs, for d-row lane%32, keys k0..k0+3 and k0+8..k0+11
       // with k0 = 16hf + 4h: two transposing reads.
       const int hf = i >> 2, dt = i & 3;
@@ -246,39 +300,68 @@ __device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16&
       vf[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
   }
-  if (SM) {
-    if (SAFE) {
-      alpha = raise_reference(w, s_cur, c);
-      w.l = __builtin_fmaf(w.l, alpha, softmax_unit(w, s_cur, p_cur, c));
-    } else {
-      float lsum = softmax_unit(w, s_cur, p_cur, c);
-      w.l += lsum;
-      w.lmax = fmaxf(w.lmax, lsum);
+  if (PRE_OUT) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      pre.k[i] = lds_read_b128(la.k[i] + NKOFF);
+      bf16x4 lo = lds_read_tr16(la.v[i][0] + NVOFF);
+      bf16x4 hi = lds_read_tr16(la.v[i][1] + NVOFF);
+      pre.v[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
   }
-  if (QK) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) s_next[v] = 0.f;
+  for (int rb = 0; rb < RB; ++rb) {
+    alpha[rb] = 1.0f;
+    if (SM) {
+      if (SAFE) {
+        alpha[rb] = raise_reference(w, rb, s_cur[rb], c);
+        w.l[rb] = __builtin_fmaf(w.l[rb], alpha[rb], softmax_unit(s_cur[rb], w.neg_mc[rb], p_cur[rb], c));
+      } else {
+        float lsum = softmax_unit(s_cur[rb], w.neg_mc[rb], p_cur[rb], c);
+        w.l[rb] += lsum;
+        w.lmax = fmaxf(w.lmax, lsum);
+      }
+    }
+    if (QK) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_next[rb][v] = 0.f;
+    }
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    if (QK) s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], w.q[i], s_next, 0, 0, 0);
-    if (PV) w.o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[i >> 2], w.o[i & 3], 0, 0, 0);
-  }
-  if (QK && SM && PV) {
-    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+    if (QK) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 3, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 4, 0);
+      for (int rb = 0; rb < RB; ++rb)
+        s_next[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], w.q[rb][i], s_next[rb], 0, 0, 0);
+    }
+    if (PV) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        w.o[rb][i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[rb][i >> 2],
+                                                                 w.o[rb][i & 3], 0, 0, 0);
     }
   }
-  if (SM) asm volatile("" : "+v"(w.l), "+v"(w.lmax), "+v"(p_cur[0]), "+v"(p_cur[1]));
+  if (QK && SM && PV) {
+    if (!PRE_IN) __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int k = 0; k < RB; ++k) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (k == RB - 1 && (i < 6 || PRE_OUT)) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 4, 0);
+      }
+    }
+  }
+  if (SM) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      asm volatile("" : "+v"(w.l[rb]), "+v"(p_cur[rb][0]), "+v"(p_cur[rb][1]));
+    asm volatile("" : "+v"(w.lmax));
+  }
   __builtin_amdgcn_sched_barrier(0);
-  return alpha;
 }
 
 // Everything a wavefront does for key tile t once tile t's scores exist:
@@ -288,12 +371,20 @@ __device__ __forceinline__ float stage(WaveState& w, const LaneAddr& la, f32x16&
 //   stage B: scores of unit 2t+3 | softmax of unit 2t+2 | PV of unit 2t+1.
 // MORE = tile t+1 exists.  KN / VC are the LDS offsets of K tile t+1 and V tile t,
 // KF / VF those of the buffers that are refilled (K tile t+2, V tile t+1).
-template <bool SAFE, bool MORE, int KN, int VC, int KF, int VF>
-__device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, const TileSeq& seq,
-                                          const char* Kb, const char* Vb, int t, int row_lim,
-                                          int wave_lo, float c, unsigned lds0, f32x16& sA,
-                                          f32x16& sB, bf16x8 (&pA)[2], bf16x8 (&pB)[2]) {
+template <int RB>
+struct LoopRegs {
+  f32x16 sA[RB], sB[RB];          // score tiles of the even / odd 32-key unit
+  bf16x8 pA[RB][2], pB[RB][2];    // their exponentials (bf16)
+};
+
+template <int RB, bool SAFE, bool MORE, int KN, int VC, int KF, int VF>
+__device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, const TileSeq& seq,
+                                          const char* Kb, const char* Vb, int t,
+                                          const int (&row_lim)[RB], int wave_lo, float c,
+                                          unsigned lds0, LoopRegs<RB>& r) {
   constexpr int H = 32 * ROWB;
+  float alpha[RB];
+  PreFrag pre;
   wait_vmcnt0();
   __builtin_amdgcn_s_barrier();
   if (t + 2 < seq.n_tiles) {
@@ -305,33 +396,35 @@ __device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, cons
     int nk0, nhi;
     seq.tile(t + 1, &nk0, &nhi);
     issue_tile(Vb, nk0, nhi, lds0 + VF, la);
-    const int nlim = row_lim < nhi ? row_lim : nhi;
-    float alpha = stage<SAFE, true, true, true, KN, VC>(w, la, sA, sB, pB, pA, c);
+    stage<RB, SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB,
+                                                                           r.pA, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    if (nk0 + 32 > wave_lo || nk0 + 32 > nhi) mask_unit(sA, nk0, nlim, la.half);
-    alpha = stage<SAFE, true, true, true, KN + H, VC + H>(w, la, sB, sA, pA, pB, c);
+    mask_if_needed<RB>(r.sA, nk0, nhi, wave_lo, row_lim, la.half);
+    stage<RB, SAFE, true, true, true, KN + H, VC + H, true>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha,
+                                                            pre);
     if (SAFE) rescale(w, alpha);
-    if (nk0 + 64 > wave_lo || nk0 + 64 > nhi) mask_unit(sB, nk0 + 32, nlim, la.half);
+    mask_if_needed<RB>(r.sB, nk0 + 32, nhi, wave_lo, row_lim, la.half);
   } else {
-    float alpha = stage<SAFE, false, true, true, 0, VC>(w, la, sA, sB, pB, pA, c);
+    stage<RB, SAFE, false, true, true, 0, VC>(w, la, r.sA, r.sB, r.pB, r.pA, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    stage<SAFE, false, false, true, 0, VC + H>(w, la, sB, sA, pA, pB, c);
+    stage<RB, SAFE, false, false, true, 0, VC + H>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha, pre);
   }
 }
 
 // Walk a tile sequence once for the calling wavefront (all four wavefronts of
 // the workgroup call this with the same sequence).
-//   row_lim     this lane's exclusive causal key bound (0 for an inactive row)
+//   row_lim     this lane's exclusive causal key bound per row block (0 = inactive row)
 //   wave_lo     smallest row_lim among the wavefront's active rows: key tiles that
 //               end at or below it need no causal mask
-template <bool SAFE>
-__device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const TileSeq& seq,
-                                         const char* Kb, const char* Vb, int row_lim, int wave_lo,
-                                         float c, unsigned lds0) {
+template <int RB, bool SAFE>
+__device__ __forceinline__ void key_loop(WaveState<RB>& w, const LaneAddr& la, const TileSeq& seq,
+                                         const char* Kb, const char* Vb, const int (&row_lim)[RB],
+                                         int wave_lo, float c, unsigned lds0) {
   const int T = seq.n_tiles;
   constexpr int K0 = LDS_K0, K1 = LDS_K1, V0 = LDS_V0, V1 = LDS_V1, H = 32 * ROWB;
-  f32x16 sA, sB;              // score tiles of the even / odd 32-key unit
-  bf16x8 pA[2], pB[2];        // their exponentials (bf16)
+  LoopRegs<RB> r;
+  float alpha[RB];
+  PreFrag pre;
   int key0, hi;
 
   // Prologue: K tile 0, V tile 0 and K tile 1 in flight; scores of tile 0.
@@ -342,51 +435,58 @@ __device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const
     int k1, h1;
     seq.tile(1, &k1, &h1);
     issue_tile(Kb, k1, h1, lds0 + K1, la);
-    wait_vmcnt8();
+    wait_vmcnt_2tiles();
   } else {
     wait_vmcnt0();
   }
   __builtin_amdgcn_s_barrier();
-  const int lim0 = row_lim < hi ? row_lim : hi;
-  stage<SAFE, true, false, false, K0, 0>(w, la, sA, sA, pA, pA, c);
-  if (key0 + 32 > wave_lo || key0 + 32 > hi) mask_unit(sA, key0, lim0, la.half);
-  stage<SAFE, true, false, false, K0 + H, 0>(w, la, sB, sA, pA, pA, c);
-  if (key0 + 64 > wave_lo || key0 + 64 > hi) mask_unit(sB, key0 + 32, lim0, la.half);
+  stage<RB, SAFE, true, false, false, K0, 0>(w, la, r.sA, r.sA, r.pA, r.pA, c, alpha, pre);
+  mask_if_needed<RB>(r.sA, key0, hi, wave_lo, row_lim, la.half);
+  stage<RB, SAFE, true, false, false, K0 + H, 0>(w, la, r.sB, r.sA, r.pA, r.pA, c, alpha, pre);
+  mask_if_needed<RB>(r.sB, key0 + 32, hi, wave_lo, row_lim, la.half);
   // first unit: its row maximum becomes the reference (nothing to rescale yet)
-  raise_reference(w, sA, c);
-  w.l = softmax_unit(w, sA, pA, c);
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    raise_reference(w, rb, r.sA[rb], c);
+    w.l[rb] = softmax_unit(r.sA[rb], w.neg_mc[rb], r.pA[rb], c);
+  }
 
   // Tile t: V tile t is consumed while K tile t+1 produces the next scores.
   // The loop is unrolled by two so that every LDS buffer offset is an immediate
   // and the accumulators flow through straight-line code.
   int t = 0;
   for (; t + 2 < T; t += 2) {
-    tile_step<SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
-    tile_step<SAFE, true, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<RB, SAFE, true, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, r);
   }
   if (T - t == 2) {
-    tile_step<SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
-    tile_step<SAFE, false, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<RB, SAFE, false, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, r);
   } else {
-    tile_step<SAFE, false, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, sA, sB, pA, pB);
+    tile_step<RB, SAFE, false, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, r);
   }
 }
 
-__device__ __forceinline__ void reset_state(WaveState& w) {
+template <int RB>
+__device__ __forceinline__ void reset_state(WaveState<RB>& w) {
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) w.o[dt][v] = 0.f;
-  w.m = -INFINITY;
-  w.neg_mc = 0.f;
-  w.l = 0.f;
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) w.o[rb][dt][v] = 0.f;
+    w.m[rb] = -INFINITY;
+    w.neg_mc[rb] = 0.f;
+    w.l[rb] = 0.f;
+  }
   w.lmax = 0.f;
 }
 
 // Attention of the workgroup's rows over a tile sequence: the fast loop, and the
 // exact loop again if any wavefront's scores left the fast loop's safe range.
-__device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const char* Kb,
-                                       const char* Vb, int row_lim, int wave_lo,
+template <int RB>
+__device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq, const char* Kb,
+                                       const char* Vb, const int (&row_lim)[RB], int wave_lo,
                                        float c, unsigned lds0) {
   LaneAddr la;
   la.tid = threadIdx.x;
@@ -415,8 +515,10 @@ __device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const c
   // Consume the Q fragments here so that the compiler places its own wait for
   // their loads before the first DMA is in flight (and none inside the loops).
 #pragma unroll
-  for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(w.q[t]));
-  key_loop<false>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(w.q[rb][t]));
+  key_loop<RB, false>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
 
   // Did any row of any wavefront leave the safe range?  One LDS word per
   // wavefront; __syncthreads() (fence + barrier) orders the tile reads before the
@@ -426,35 +528,37 @@ __device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const c
   LDS_AS int* flags = (LDS_AS int*)(size_t)lds0;
   if (lane == 0) flags[la.tid >> 6] = bad ? 1 : 0;
   __syncthreads();
-  const int any_bad = flags[0] | flags[1] | flags[2] | flags[3];
+  int any_bad = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) any_bad |= flags[i];
   __syncthreads();
   if (__builtin_expect(any_bad != 0, 0)) {
     reset_state(w);
-    key_loop<true>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
+    key_loop<RB, true>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
   }
 }
 
-__device__ __forceinline__ void load_q(WaveState& w, const char* qrow, int half) {
+template <int RB>
+__device__ __forceinline__ void load_q(WaveState<RB>& w, int rb, const char* qrow, int half) {
 #pragma unroll
-  for (int t = 0; t < 8; ++t) w.q[t] = *(const bf16x8*)(qrow + (16 * t + 8 * half) * 2);
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) w.o[dt][v] = 0.f;
-  w.m = -INFINITY;
-  w.neg_mc = 0.f;
-  w.l = 0.f;
-  w.lmax = 0.f;
+  for (int t = 0; t < 8; ++t) w.q[rb][t] = *(const bf16x8*)(qrow + (16 * t + 8 * half) * 2);
 }
+
+// Row block g of a workgroup (g = wave * RB + rb, NW * RB of them) is head g % hpw of
+// the workgroup's head group and token block g / hpw: the heads of a KV group
+// come first, so that a wavefront's row blocks share their tokens (and their
+// causal frontier) whenever the group has at least RB heads.
 
 // ------------------------------------------------------------------ phase 1
 // grid.x enumerates (kv head fastest, then work items); see launch_phase1_bf16.
-__global__ __launch_bounds__(256, 2) void phase1_bf16_kernel(Phase1Args a, int hpw, int tpb, int n_hs) {
+template <int RB>
+__global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1Args a, int hpw,
+                                                                           int tpb, int n_hs) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const Geom& g = a.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, i32 = lane & 31;
-  const int tm = 32 * (4 / hpw);                 // tokens per workgroup
+  const int tm = 32 * (NW * RB / hpw);           // tokens per workgroup
 
   // work decode: kv head fastest (one KV head per XCD when Hkv is a multiple of
   // 8), then batch, head sub-group, tile within block (late = heavy first),
@@ -471,18 +575,30 @@ __global__ __launch_bounds__(256, 2) void phase1_bf16_kernel(Phase1Args a, int h
   int e = (int)((int64_t)s + g.b < g.L ? s + g.b : g.L);
   int row0 = s + t * tm;
   if (row0 >= e) return;                         // tile beyond a short block
-
-  int head = kvh * g.G + hs * hpw + wave % hpw;
-  int tok0 = row0 + 32 * (wave / hpw);
-  int tok = tok0 + i32;
-  bool active = tok < e;
   int wg_last = row0 + tm < e ? row0 + tm : e;   // exclusive bound of the workgroup's tokens
 
   const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
-  WaveState w;
-  int qtok = active ? tok : (tok0 < e ? tok0 : e - 1);
-  load_q(w, (const char*)a.Q + (((size_t)beta * g.L + qtok) * g.Hq + head) * ROWB, half);
+  WaveState<RB> w;
+  int head[RB], tok[RB], row_lim[RB];
+  bool active[RB];
+  int wave_lo = 0x7fffffff;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    int gb = wave * RB + rb;
+    head[rb] = kvh * g.G + hs * hpw + gb % hpw;
+    int tok0 = row0 + 32 * (gb / hpw);
+    tok[rb] = tok0 + i32;
+    active[rb] = tok[rb] < e;
+    int qtok = active[rb] ? tok[rb] : (tok0 < e ? tok0 : e - 1);
+    load_q(w, rb, (const char*)a.Q + (((size_t)beta * g.L + qtok) * g.Hq + head[rb]) * ROWB, half);
+    // a row sees key k iff k < tok + 1; anchor keys always qualify (a <= b <= tok)
+    row_lim[rb] = active[rb] ? tok[rb] + 1 : 0;
+    int lo = tok0 < e ? tok0 + 1 : 0;
+    wave_lo = lo < wave_lo ? lo : wave_lo;
+  }
+  wave_lo = __builtin_amdgcn_readfirstlane(wave_lo);   // wave-uniform
+  reset_state(w);
 
   TileSeq seq;
   seq.a_hi = i > 0 ? (int)g.a : 0;
@@ -491,28 +607,28 @@ __global__ __launch_bounds__(256, 2) void phase1_bf16_kernel(Phase1Args a, int h
   seq.loc_hi = wg_last;
   seq.n_tiles = seq.n_a + (wg_last - s + TKEYS - 1) / TKEYS;
 
-  // a row sees key k iff k < tok + 1; anchor keys always qualify (a <= b <= tok)
-  int row_lim = active ? tok + 1 : 0;
-  int wave_lo = tok0 < e ? tok0 + 1 : 0;
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
+  attend<RB>(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
-  float l_tot = pair_sum(w.l);
-  if (active) {
-    float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    char* orow = (char*)a.O + (((size_t)beta * g.L + tok) * g.Hq + head) * ROWB;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+  for (int rb = 0; rb < RB; ++rb) {
+    float l_tot = pair_sum(w.l[rb]);
+    if (active[rb]) {
+      float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      char* orow = (char*)a.O + (((size_t)beta * g.L + tok[rb]) * g.Hq + head[rb]) * ROWB;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        bf16x4 v;
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = (__bf16)(w.o[dt][4 * j + k] * inv);
-        *(bf16x4*)(orow + (32 * dt + 8 * j + 4 * half) * 2) = v;
-      }
-    if (a.LSE && half == 0)
-      a.LSE[((size_t)beta * g.Hq + head) * g.L + tok] =
-          l_tot > 0.f ? (w.m * g.scale * LOG2E + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
+        for (int j = 0; j < 4; ++j) {
+          bf16x4 v;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[k] = (__bf16)(w.o[rb][dt][4 * j + k] * inv);
+          *(bf16x4*)(orow + (32 * dt + 8 * j + 4 * half) * 2) = v;
+        }
+      if (a.LSE && half == 0)
+        a.LSE[((size_t)beta * g.Hq + head[rb]) * g.L + tok[rb]] =
+            l_tot > 0.f ? (w.m[rb] * g.scale * LOG2E + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
+    }
   }
 }
 
@@ -520,13 +636,15 @@ __global__ __launch_bounds__(256, 2) void phase1_bf16_kernel(Phase1Args a, int h
 // Local attention (Eq. 1) and log-sum-exp (log of Eq. 2) of a row tile over one
 // split of the cache.  grid.x = ((batch * s_total + split) * n_hs + hs) * row_tiles + tile,
 // grid.y = kv head.
-__global__ __launch_bounds__(256, 2) void phase2_rows_bf16_kernel(Phase2Args a, int hpw, int n_hs,
-                                                                  int row_tiles) {
+template <int RB>
+__global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase2_rows_bf16_kernel(Phase2Args a, int hpw,
+                                                                                int n_hs,
+                                                                                int row_tiles) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const Geom& g = a.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, i32 = lane & 31;
-  const int tm = 32 * (4 / hpw);
+  const int tm = 32 * (NW * RB / hpw);
 
   int id = blockIdx.x;
   int tt = id % row_tiles; id /= row_tiles;
@@ -535,10 +653,6 @@ __global__ __launch_bounds__(256, 2) void phase2_rows_bf16_kernel(Phase2Args a, 
   int beta = id / a.plan.s_total;
   int kvh = blockIdx.y;
 
-  int head = kvh * g.G + hs * hpw + wave % hpw;
-  int j0 = tt * tm + 32 * (wave / hpw);
-  int j = j0 + i32;
-  bool active = j < a.q_len;
   int total = (int)(a.cache_len + a.q_len);
   int64_t lo64, hi64;
   split_range(a.plan, g.L, g.b, total, sp, &lo64, &hi64);
@@ -546,73 +660,98 @@ __global__ __launch_bounds__(256, 2) void phase2_rows_bf16_kernel(Phase2Args a, 
 
   const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
-  WaveState w;
-  int qj = active ? j : (j0 < a.q_len ? j0 : a.q_len - 1);
-  load_q(w, (const char*)a.Qq + (((size_t)beta * a.q_len + qj) * g.Hq + head) * ROWB, half);
+  WaveState<RB> w;
+  int head[RB], jrow[RB], row_lim[RB];
+  bool active[RB];
+  int wave_lo = 0x7fffffff;
+  const int cl = (int)a.cache_len;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    int gb = wave * RB + rb;
+    head[rb] = kvh * g.G + hs * hpw + gb % hpw;
+    int j0 = tt * tm + 32 * (gb / hpw);
+    jrow[rb] = j0 + i32;
+    active[rb] = jrow[rb] < a.q_len;
+    int qj = active[rb] ? jrow[rb] : (j0 < a.q_len ? j0 : a.q_len - 1);
+    load_q(w, rb, (const char*)a.Qq + (((size_t)beta * a.q_len + qj) * g.Hq + head[rb]) * ROWB, half);
+    // token j sees cache rows [0, cache_len + j]
+    row_lim[rb] = active[rb] ? cl + jrow[rb] + 1 : 0;
+    int l0 = j0 < a.q_len ? cl + j0 + 1 : 0;
+    wave_lo = l0 < wave_lo ? l0 : wave_lo;
+  }
+  wave_lo = __builtin_amdgcn_readfirstlane(wave_lo);   // wave-uniform
+  reset_state(w);
 
   TileSeq seq;
   seq.a_hi = 0; seq.n_a = 0; seq.loc_lo = lo; seq.loc_hi = hi;
   seq.n_tiles = hi > lo ? (hi - lo + TKEYS - 1) / TKEYS : 0;
 
-  // token j sees cache rows [0, cache_len + j]
-  int cl = (int)a.cache_len;
-  int row_lim = active ? cl + j + 1 : 0;
-  int wave_lo = j0 < a.q_len ? cl + j0 + 1 : 0;
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
+  attend<RB>(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
-  float l_tot = pair_sum(w.l);
-  if (active) {
-    float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    size_t r = (((size_t)beta * a.plan.s_total + sp) * g.Hq + head) * a.q_len + j;
-    float* orow = a.O_sub + r * D;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+  for (int rb = 0; rb < RB; ++rb) {
+    float l_tot = pair_sum(w.l[rb]);
+    if (active[rb]) {
+      float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      size_t r = (((size_t)beta * a.plan.s_total + sp) * g.Hq + head[rb]) * a.q_len + jrow[rb];
+      float* orow = a.O_sub + r * D;
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        f32x4 v;
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = w.o[dt][4 * jj + k] * inv;
-        *(f32x4*)(orow + 32 * dt + 8 * jj + 4 * half) = v;
-      }
-    if (half == 0)
-      a.LSE_sub[r] = l_tot > 0.f ? (w.m * g.scale * LOG2E + __builtin_amdgcn_logf(l_tot)) * LN2
-                                 : -INFINITY;
+        for (int jj = 0; jj < 4; ++jj) {
+          f32x4 v;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[k] = w.o[rb][dt][4 * jj + k] * inv;
+          *(f32x4*)(orow + 32 * dt + 8 * jj + 4 * half) = v;
+        }
+      if (half == 0)
+        a.LSE_sub[r] = l_tot > 0.f ? (w.m[rb] * g.scale * LOG2E + __builtin_amdgcn_logf(l_tot)) * LN2
+                                   : -INFINITY;
+    }
   }
 }
 
 }  // namespace
 
+// Row blocks per wavefront of the two row-tiled kernels.
+constexpr int P1_RB = 1;
+constexpr int P2_RB = 1;
+
+// 32-row blocks per workgroup of the phase-2 row-tiled kernel (the split plan
+// sizes its grid with it).
+int flash_row_blocks() { return NW * P2_RB; }
+
 hipError_t launch_phase1_bf16(const Phase1Args& a, hipStream_t st) {
   const Geom& g = a.g;
-  int hpw = heads_per_workgroup(g.G);
-  int tm = 32 * (4 / hpw);
+  int hpw = heads_per_workgroup(g.G, NW * P1_RB);
+  int tm = 32 * (NW * P1_RB / hpw);
   int n_hs = g.G / hpw;
   int64_t n = (g.L + g.b - 1) / g.b;
   int64_t bmax = g.b < g.L ? g.b : g.L;
   int tpb = (int)((bmax + tm - 1) / tm);
   int64_t wgs = (int64_t)g.Hkv * g.B * n_hs * tpb * n;
   if (wgs > 0x7fffffff) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute((const void*)phase1_bf16_kernel,
+  hipError_t e = hipFuncSetAttribute((const void*)phase1_bf16_kernel<P1_RB>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
   if (e != hipSuccess) return e;
-  phase1_bf16_kernel<<<dim3((unsigned)wgs), 256, 4 * TILEB, st>>>(a, hpw, tpb, n_hs);
+  phase1_bf16_kernel<P1_RB><<<dim3((unsigned)wgs), NT, 4 * TILEB, st>>>(a, hpw, tpb, n_hs);
   return hipGetLastError();
 }
 
 hipError_t launch_phase2_rows_bf16(const Phase2Args& a, hipStream_t st) {
   const Geom& g = a.g;
-  int hpw = heads_per_workgroup(g.G);
-  int tm = 32 * (4 / hpw);
+  int hpw = heads_per_workgroup(g.G, flash_row_blocks());
+  int tm = 32 * (flash_row_blocks() / hpw);
   int n_hs = g.G / hpw;
   int row_tiles = (a.q_len + tm - 1) / tm;
   int64_t gx = (int64_t)g.B * a.plan.s_total * n_hs * row_tiles;
   if (gx > 0x7fffffff || g.Hkv > 65535) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute((const void*)phase2_rows_bf16_kernel,
+  hipError_t e = hipFuncSetAttribute((const void*)phase2_rows_bf16_kernel<P2_RB>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
   if (e != hipSuccess) return e;
-  phase2_rows_bf16_kernel<<<dim3((unsigned)gx, (unsigned)g.Hkv), 256, 4 * TILEB, st>>>(a, hpw, n_hs,
-                                                                                       row_tiles);
+  phase2_rows_bf16_kernel<P2_RB><<<dim3((unsigned)gx, (unsigned)g.Hkv), NT, 4 * TILEB, st>>>(
+      a, hpw, n_hs, row_tiles);
   return hipGetLastError();
 }
 
