@@ -31,6 +31,55 @@ def phase1_mask(L: int, b: int, a: int) -> np.ndarray:
     return mask
 
 
+def previous_anchor_mask(L: int, b: int, a: int) -> np.ndarray:
+    """Token-level mask of the "previous block as anchor" ablation (Section 4.1):
+    block 1 is a lower triangle; a later block sees the `a` columns just left of
+    its own columns, all of them, and a lower triangle on its own columns."""
+    mask = np.zeros((L, L), dtype=bool)
+    n = -(-L // b)
+    for i in range(n):
+        s, e = i * b, min((i + 1) * b, L)
+        for p in range(s, e):
+            for k in range(s, p + 1):
+                mask[p, k] = True
+            if i > 0:
+                for k in range(s - a, s):
+                    mask[p, k] = True
+    return mask
+
+
+def external_anchor_dense(Q, K, V, Ka, Va, b: int, scale=None):
+    """Phase 1 with separately given anchor keys/values, by brute force: for
+    every block after the first, lay out the sequence [anchor; block] as Figure 2
+    draws it, run dense causal-within-[anchor; block] attention with an explicit
+    mask, and keep the rows of the block.  Ka, Va [B, a, Hkv, d].
+    Returns O [B, L, Hq, d], LSE [B, Hq, L]."""
+    B, L, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    G = Hq // Hkv
+    a = Ka.shape[1]
+    sc = 1.0 / math.sqrt(d) if scale is None else scale
+    n = -(-L // b)
+    O = np.zeros((B, L, Hq, d))
+    LSE = np.zeros((B, Hq, L))
+    for beta in range(B):
+        for h in range(Hq):
+            g = h // G
+            for i in range(n):
+                s, e = i * b, min((i + 1) * b, L)
+                rows = e - s
+                pre = 0 if i == 0 else a
+                kk = K[beta, s:e, g] if i == 0 else np.concatenate([Ka[beta, :, g], K[beta, s:e, g]])
+                vv = V[beta, s:e, g] if i == 0 else np.concatenate([Va[beta, :, g], V[beta, s:e, g]])
+                mask = np.zeros((rows, pre + rows), dtype=bool)
+                for r in range(rows):
+                    mask[r, :pre + r + 1] = True
+                o, l = dense_masked_attention(Q[beta, s:e, h], kk, vv, mask, sc)
+                O[beta, s:e, h] = o
+                LSE[beta, h, s:e] = l
+    return O, LSE
+
+
 def dense_masked_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                            mask: np.ndarray, scale: float):
     """softmax(mask(scale * q k^T)) v for one head.  q [Tq, d], k, v [Tk, d],

@@ -130,6 +130,66 @@ def phase1_full(Q, K, V, b: int, a: int, scale: Optional[float] = None
     return O, LSE
 
 
+# Anchor variants of the ablation study (Section 4.1, "Position and Content of
+# Anchor Block"; Section 4.2 for the anchor size).  Block 1 is plain causal
+# attention in every variant; the variants differ in what prefixes a later block.
+ANCHOR_FIRST = 0      # the method itself: first `a` tokens of block 1
+ANCHOR_PREVIOUS = 1   # "previous block as anchor": the `a` tokens just before the block
+ANCHOR_EXTERNAL = 2   # anchor keys/values given separately (other content, or the
+                      # first block's content encoded at other position ids)
+
+
+def anchor_key_rows(i: int, b: int, a: int, mode: int) -> np.ndarray:
+    """Context positions that prefix 0-based block i >= 1 when the anchor is
+    taken from the context itself."""
+    if mode == ANCHOR_FIRST:
+        return np.arange(0, a)
+    if mode == ANCHOR_PREVIOUS:
+        return np.arange(i * b - a, i * b)
+    raise ValueError("anchor rows are context positions only for FIRST / PREVIOUS")
+
+
+def phase1_row_variant(Q, K, V, beta: int, h: int, p: int, b: int, a: int, mode: int,
+                       K_anchor=None, V_anchor=None, scale: Optional[float] = None
+                       ) -> Tuple[np.ndarray, float]:
+    """Phase-1 row under an anchor variant.  The row attends to the anchor's
+    `a` keys (all visible) followed by its own block up to itself; for
+    ANCHOR_EXTERNAL the anchor keys/values are K_anchor, V_anchor [B, a, Hkv, d]."""
+    B, L, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    g = h // (Hq // Hkv)
+    if not (0 <= a <= b):
+        raise ValueError("anchor must satisfy 0 <= a <= b")
+    i = p // b
+    s = i * b
+    own = np.arange(s, p + 1)
+    sc = softmax_scale(d, scale)
+    if i == 0:
+        return attend(Q[beta, p, h], K[beta, own, g], V[beta, own, g], sc)
+    if mode == ANCHOR_EXTERNAL:
+        if K_anchor.shape[1] != a or V_anchor.shape[1] != a:
+            raise ValueError("external anchor must hold exactly `a` tokens")
+        Kv = np.concatenate([np.asarray(K_anchor[beta, :, g], F64), np.asarray(K[beta, own, g], F64)])
+        Vv = np.concatenate([np.asarray(V_anchor[beta, :, g], F64), np.asarray(V[beta, own, g], F64)])
+        return attend(Q[beta, p, h], Kv, Vv, sc)
+    ks = np.concatenate([anchor_key_rows(i, b, a, mode), own])
+    return attend(Q[beta, p, h], K[beta, ks, g], V[beta, ks, g], sc)
+
+
+def phase1_full_variant(Q, K, V, b: int, a: int, mode: int, K_anchor=None, V_anchor=None,
+                        scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Every context row under an anchor variant: O [B, L, Hq, d], LSE [B, Hq, L]."""
+    B, L, Hq, d = Q.shape
+    O = np.zeros((B, L, Hq, V.shape[3]), F64)
+    LSE = np.zeros((B, Hq, L), F64)
+    for beta in range(B):
+        for h in range(Hq):
+            for p in range(L):
+                O[beta, p, h], LSE[beta, h, p] = phase1_row_variant(
+                    Q, K, V, beta, h, p, b, a, mode, K_anchor, V_anchor, scale)
+    return O, LSE
+
+
 def kv_cache(K, V, capacity: int) -> Tuple[np.ndarray, np.ndarray]:
     """KV cache after phase 1 (Algorithm 1: anchor KV discarded, block KV
     appended): every context token once, in order, rows beyond L zero.
