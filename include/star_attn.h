@@ -53,7 +53,15 @@ enum {
   STAR_ATTN_ERR_CACHE_OVERFLOW = -6,       /* ctx_len or cache_len + q_len exceeds cache_capacity */
   STAR_ATTN_ERR_WORKSPACE_TOO_SMALL = -7,
   STAR_ATTN_ERR_LAUNCH_FAILED = -8,        /* the HIP runtime refused a launch */
-  STAR_ATTN_ERR_MISALIGNED = -9            /* a tensor pointer is not 16-byte aligned */
+  STAR_ATTN_ERR_MISALIGNED = -9,           /* a tensor pointer is not 16-byte aligned */
+  STAR_ATTN_ERR_INVALID_MODE = -10         /* anchor_mode is none of STAR_ATTN_ANCHOR_* */
+};
+
+/* What prefixes every context block after the first in phase 1. */
+enum {
+  STAR_ATTN_ANCHOR_FIRST = 0,     /* the method: the first a context tokens (Section 2.1) */
+  STAR_ATTN_ANCHOR_PREVIOUS = 1,  /* ablation: the a tokens just before the block (Section 4.1) */
+  STAR_ATTN_ANCHOR_EXTERNAL = 2   /* ablation: anchor K/V handed in separately (Section 4.1) */
 };
 
 /* Problem shape; sizes in elements / tokens. */
@@ -104,6 +112,40 @@ int star_attn_phase1(const star_attn_shape* shape,
                      void* O_ctx, float* LSE_ctx,
                      void* K_cache, void* V_cache,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Phase 1 under the anchor variants of the ablation study (Section 4.1,
+ * "Position and Content of Anchor Block"; Section 4.2 varies a).  Block 0 is
+ * plain causal attention in every mode.  Context row p of block i >= 1 attends to
+ *   STAR_ATTN_ANCHOR_FIRST     keys [0, a) and [i*b, p]   (== star_attn_phase1),
+ *   STAR_ATTN_ANCHOR_PREVIOUS  keys [i*b - a, p]          (the previous block's
+ *                              last a tokens serve as anchor),
+ *   STAR_ATTN_ANCHOR_EXTERNAL  all a rows of K_anchor / V_anchor, then keys
+ *                              [i*b, p] of K / V: the anchor's content, or the
+ *                              position ids it was encoded with, differ from
+ *                              the context's first tokens.
+ * a = 0 is "no anchor" in every mode.  The caches receive the context tokens
+ * only, exactly as in star_attn_phase1.
+ *
+ *   K_anchor, V_anchor  in  [B, a, Hkv, d], dtype of the inputs; read only in
+ *                 mode EXTERNAL with a > 0 (else may be NULL)
+ *   workspace     mode EXTERNAL: at least
+ *                 star_attn_phase1_workspace_bytes(shape, mode) bytes, 256-byte
+ *                 aligned (holds a head-major copy of the anchor; scratch);
+ *                 other modes: unused, may be NULL / 0
+ *   other arguments as in star_attn_phase1
+ * Errors as in star_attn_phase1, plus STAR_ATTN_ERR_INVALID_MODE and
+ * STAR_ATTN_ERR_WORKSPACE_TOO_SMALL.
+ */
+int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode,
+                            const void* Q, const void* K, const void* V,
+                            const void* K_anchor, const void* V_anchor,
+                            void* O_ctx, float* LSE_ctx,
+                            void* K_cache, void* V_cache,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Workspace bytes star_attn_phase1_anchor needs (0 unless mode EXTERNAL; 0 for an invalid shape). */
+size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode);
 
 /*
  * Phase 2: query encoding or one decode step (Section 2.2; Eq. 1-4; Algorithm 2).

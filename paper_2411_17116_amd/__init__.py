@@ -6,6 +6,7 @@ step of the computation runs in the HIP kernels of libstarattn.so.  There is no
 CPU or PyTorch fallback: if the library is missing or fails, an error is raised.
 """
 from .binding import (  # noqa: F401
-    BF16, F32, StarAttnError, StarShape, lib_path, load_library, phase1, phase2,
-    status_string, workspace_bytes, kernel_path, alloc_cache, alloc_workspace,
+    BF16, F32, ANCHOR_FIRST, ANCHOR_PREVIOUS, ANCHOR_EXTERNAL, StarAttnError, StarShape, lib_path,
+    load_library, phase1, phase1_anchor, phase1_workspace_bytes, phase2, status_string,
+    workspace_bytes, kernel_path, alloc_cache, alloc_workspace,
 )

@@ -9,6 +9,9 @@ import torch
 
 F32 = 0
 BF16 = 1
+ANCHOR_FIRST = 0
+ANCHOR_PREVIOUS = 1
+ANCHOR_EXTERNAL = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -63,6 +66,11 @@ def load_library():
     lib.star_attn_workspace_bytes.argtypes = [P, i64]
     lib.star_attn_phase1.restype = ctypes.c_int
     lib.star_attn_phase1.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.star_attn_phase1_anchor.restype = ctypes.c_int
+    lib.star_attn_phase1_anchor.argtypes = [P, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                            vp, sz, vp]
+    lib.star_attn_phase1_workspace_bytes.restype = sz
+    lib.star_attn_phase1_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.star_attn_phase2.restype = ctypes.c_int
     lib.star_attn_phase2.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.star_attn_status_string.restype = ctypes.c_char_p
@@ -126,6 +134,21 @@ def phase1(shape: StarShape, Q, K, V, O_ctx, K_cache, V_cache, LSE_ctx=None,
     rc = load_library().star_attn_phase1(
         ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(O_ctx), _ptr(LSE_ctx),
         _ptr(K_cache), _ptr(V_cache), _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)
+
+
+def phase1_workspace_bytes(shape: StarShape, anchor_mode: int) -> int:
+    return int(load_library().star_attn_phase1_workspace_bytes(ctypes.byref(shape), int(anchor_mode)))
+
+
+def phase1_anchor(shape: StarShape, anchor_mode: int, Q, K, V, O_ctx, K_cache, V_cache,
+                  K_anchor=None, V_anchor=None, LSE_ctx=None, workspace=None, stream=None) -> None:
+    """star_attn_phase1_anchor: phase 1 under an anchor variant of the ablation study."""
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load_library().star_attn_phase1_anchor(
+        ctypes.byref(shape), int(anchor_mode), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_anchor),
+        _ptr(V_anchor), _ptr(O_ctx), _ptr(LSE_ctx), _ptr(K_cache), _ptr(V_cache),
+        _ptr(workspace), ws_n, _stream(stream))
     _check(rc)
 
 

@@ -123,6 +123,13 @@ static size_t plan_bytes(const star_attn_shape* s, const SplitPlan& p, int64_t q
 
 static bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// Bytes of one head-major copy of the external anchor (K or V), 256-byte padded.
+static size_t anchor_copy_bytes(const star_attn_shape* s) {
+  size_t es = s->dtype == STAR_ATTN_F32 ? 4 : 2;
+  size_t n = (size_t)s->batch * (size_t)s->n_kv_heads * (size_t)s->anchor * (size_t)s->head_dim * es;
+  return (n + 255) & ~(size_t)255;
+}
+
 }  // namespace star
 
 using namespace star;
@@ -155,16 +162,32 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
   return best;
 }
 
-int star_attn_phase1(const star_attn_shape* shape, const void* Q, const void* K, const void* V,
-                     void* O_ctx, float* LSE_ctx, void* K_cache, void* V_cache,
-                     void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
+size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode) {
+  if (validate_shape(shape) != STAR_ATTN_OK) return 0;
+  return anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ? 2 * anchor_copy_bytes(shape) : 0;
+}
+
+int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode, const void* Q,
+                            const void* K, const void* V, const void* K_anchor,
+                            const void* V_anchor, void* O_ctx, float* LSE_ctx, void* K_cache,
+                            void* V_cache, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
   int rc = validate_shape(shape);
   if (rc != STAR_ATTN_OK) return rc;
+  if (anchor_mode != STAR_ATTN_ANCHOR_FIRST && anchor_mode != STAR_ATTN_ANCHOR_PREVIOUS &&
+      anchor_mode != STAR_ATTN_ANCHOR_EXTERNAL)
+    return STAR_ATTN_ERR_INVALID_MODE;
   if (!Q || !K || !V || !O_ctx || !K_cache || !V_cache) return STAR_ATTN_ERR_NULL_POINTER;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O_ctx) ||
       misaligned(K_cache) || misaligned(V_cache) || ((uintptr_t)LSE_ctx & 3u))
     return STAR_ATTN_ERR_MISALIGNED;
+  const bool ext = anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL && shape->anchor > 0;
+  if (ext) {
+    if (!K_anchor || !V_anchor || !workspace) return STAR_ATTN_ERR_NULL_POINTER;
+    if (misaligned(K_anchor) || misaligned(V_anchor) || ((uintptr_t)workspace & 255u))
+      return STAR_ATTN_ERR_MISALIGNED;
+    if (workspace_bytes < 2 * anchor_copy_bytes(shape)) return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
+  }
   Geom g = make_geom(shape);
   hipStream_t st = (hipStream_t)hip_stream;
   // Algorithm 1: keep the K/V of every block once (anchor copies never exist here).
@@ -172,8 +195,27 @@ int star_attn_phase1(const star_attn_shape* shape, const void* Q, const void* K,
     return STAR_ATTN_ERR_LAUNCH_FAILED;
   Phase1Args a;
   a.g = g; a.Q = Q; a.O = O_ctx; a.LSE = LSE_ctx; a.Kc = K_cache; a.Vc = V_cache;
+  a.anchor_mode = anchor_mode; a.Ka = nullptr; a.Va = nullptr;
+  if (ext) {
+    // the separately given anchor, head-major like the caches: [B, Hkv, a, d]
+    Geom ga = g;
+    ga.cap = g.a;
+    char* wk = (char*)workspace;
+    char* wv = wk + anchor_copy_bytes(shape);
+    if (launch_cache_write(ga, shape->dtype, K_anchor, V_anchor, wk, wv, g.a, 0, st) != hipSuccess)
+      return STAR_ATTN_ERR_LAUNCH_FAILED;
+    a.Ka = wk; a.Va = wv;
+  }
   hipError_t e = shape->dtype == STAR_ATTN_F32 ? launch_phase1_f32(a, st) : launch_phase1_bf16(a, st);
   return e == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
+}
+
+int star_attn_phase1(const star_attn_shape* shape, const void* Q, const void* K, const void* V,
+                     void* O_ctx, float* LSE_ctx, void* K_cache, void* V_cache,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  return star_attn_phase1_anchor(shape, STAR_ATTN_ANCHOR_FIRST, Q, K, V, nullptr, nullptr, O_ctx,
+                                 LSE_ctx, K_cache, V_cache, nullptr, 0, hip_stream);
 }
 
 int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
@@ -237,6 +279,7 @@ const char* star_attn_status_string(int status) {
     case STAR_ATTN_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case STAR_ATTN_ERR_LAUNCH_FAILED: return "kernel launch failed";
     case STAR_ATTN_ERR_MISALIGNED: return "pointer not sufficiently aligned";
+    case STAR_ATTN_ERR_INVALID_MODE: return "unknown anchor mode";
     default: return "unknown status";
   }
 }

@@ -106,18 +106,26 @@ __device__ __forceinline__ void wait_vmcnt_2tiles() {
   else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
 }
 
-// Sequence of key tiles a workgroup walks: first the tiles of [0, a_hi)
-// (n_a of them), then the tiles of [loc_lo, loc_hi).
+// Sequence of key tiles a workgroup walks: first the tiles of the anchor rows
+// [a_lo, a_hi) of Ka / Va (n_a of them), then the tiles of rows [loc_lo, loc_hi)
+// of Kl / Vl.  All four are bases of one (batch, KV head), rows of ROWB bytes.
 struct TileSeq {
   int n_a;
   int n_tiles;
+  int a_lo;
   int a_hi;
   int loc_lo;
   int loc_hi;
+  const char* Ka;
+  const char* Va;
+  const char* Kl;
+  const char* Vl;
   __device__ __forceinline__ void tile(int idx, int* key0, int* hi) const {
-    if (idx < n_a) { *key0 = idx * TKEYS; *hi = a_hi; }
+    if (idx < n_a) { *key0 = a_lo + idx * TKEYS; *hi = a_hi; }
     else { *key0 = loc_lo + (idx - n_a) * TKEYS; *hi = loc_hi; }
   }
+  __device__ __forceinline__ const char* kbase(int idx) const { return idx < n_a ? Ka : Kl; }
+  __device__ __forceinline__ const char* vbase(int idx) const { return idx < n_a ? Va : Vl; }
 };
 
 // RB = row blocks of 32 query rows per wavefront.  Every K / V^T fragment read
@@ -379,8 +387,7 @@ struct LoopRegs {
 
 template <int RB, bool SAFE, bool MORE, int KN, int VC, int KF, int VF>
 __device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, const TileSeq& seq,
-                                          const char* Kb, const char* Vb, int t,
-                                          const int (&row_lim)[RB], int wave_lo, float c,
+                                          int t, const int (&row_lim)[RB], int wave_lo, float c,
                                           unsigned lds0, LoopRegs<RB>& r) {
   constexpr int H = 32 * ROWB;
   float alpha[RB];
@@ -390,12 +397,12 @@ __device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, 
   if (t + 2 < seq.n_tiles) {
     int k2, h2;
     seq.tile(t + 2, &k2, &h2);
-    issue_tile(Kb, k2, h2, lds0 + KF, la);
+    issue_tile(seq.kbase(t + 2), k2, h2, lds0 + KF, la);
   }
   if (MORE) {
     int nk0, nhi;
     seq.tile(t + 1, &nk0, &nhi);
-    issue_tile(Vb, nk0, nhi, lds0 + VF, la);
+    issue_tile(seq.vbase(t + 1), nk0, nhi, lds0 + VF, la);
     stage<RB, SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB,
                                                                            r.pA, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
@@ -418,8 +425,8 @@ __device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, 
 //               end at or below it need no causal mask
 template <int RB, bool SAFE>
 __device__ __forceinline__ void key_loop(WaveState<RB>& w, const LaneAddr& la, const TileSeq& seq,
-                                         const char* Kb, const char* Vb, const int (&row_lim)[RB],
-                                         int wave_lo, float c, unsigned lds0) {
+                                         const int (&row_lim)[RB], int wave_lo, float c,
+                                         unsigned lds0) {
   const int T = seq.n_tiles;
   constexpr int K0 = LDS_K0, K1 = LDS_K1, V0 = LDS_V0, V1 = LDS_V1, H = 32 * ROWB;
   LoopRegs<RB> r;
@@ -429,12 +436,12 @@ __device__ __forceinline__ void key_loop(WaveState<RB>& w, const LaneAddr& la, c
 
   // Prologue: K tile 0, V tile 0 and K tile 1 in flight; scores of tile 0.
   seq.tile(0, &key0, &hi);
-  issue_tile(Kb, key0, hi, lds0 + K0, la);
-  issue_tile(Vb, key0, hi, lds0 + V0, la);
+  issue_tile(seq.kbase(0), key0, hi, lds0 + K0, la);
+  issue_tile(seq.vbase(0), key0, hi, lds0 + V0, la);
   if (T > 1) {
     int k1, h1;
     seq.tile(1, &k1, &h1);
-    issue_tile(Kb, k1, h1, lds0 + K1, la);
+    issue_tile(seq.kbase(1), k1, h1, lds0 + K1, la);
     wait_vmcnt_2tiles();
   } else {
     wait_vmcnt0();
@@ -456,14 +463,14 @@ __device__ __forceinline__ void key_loop(WaveState<RB>& w, const LaneAddr& la, c
   // and the accumulators flow through straight-line code.
   int t = 0;
   for (; t + 2 < T; t += 2) {
-    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, r);
-    tile_step<RB, SAFE, true, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, r);
+    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<RB, SAFE, true, K0, V1, K1, V0>(w, la, seq, t + 1, row_lim, wave_lo, c, lds0, r);
   }
   if (T - t == 2) {
-    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, r);
-    tile_step<RB, SAFE, false, K0, V1, K1, V0>(w, la, seq, Kb, Vb, t + 1, row_lim, wave_lo, c, lds0, r);
+    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<RB, SAFE, false, K0, V1, K1, V0>(w, la, seq, t + 1, row_lim, wave_lo, c, lds0, r);
   } else {
-    tile_step<RB, SAFE, false, K1, V0, K0, V1>(w, la, seq, Kb, Vb, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<RB, SAFE, false, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
   }
 }
 
@@ -485,9 +492,9 @@ __device__ __forceinline__ void reset_state(WaveState<RB>& w) {
 // Attention of the workgroup's rows over a tile sequence: the fast loop, and the
 // exact loop again if any wavefront's scores left the fast loop's safe range.
 template <int RB>
-__device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq, const char* Kb,
-                                       const char* Vb, const int (&row_lim)[RB], int wave_lo,
-                                       float c, unsigned lds0) {
+__device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq,
+                                       const int (&row_lim)[RB], int wave_lo, float c,
+                                       unsigned lds0) {
   LaneAddr la;
   la.tid = threadIdx.x;
   const int lane = la.tid & 63;
@@ -518,7 +525,7 @@ __device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq, con
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(w.q[rb][t]));
-  key_loop<RB, false>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
+  key_loop<RB, false>(w, la, seq, row_lim, wave_lo, c, lds0);
 
   // Did any row of any wavefront leave the safe range?  One LDS word per
   // wavefront; __syncthreads() (fence + barrier) orders the tile reads before the
@@ -534,7 +541,7 @@ __device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq, con
   __syncthreads();
   if (__builtin_expect(any_bad != 0, 0)) {
     reset_state(w);
-    key_loop<RB, true>(w, la, seq, Kb, Vb, row_lim, wave_lo, c, lds0);
+    key_loop<RB, true>(w, la, seq, row_lim, wave_lo, c, lds0);
   }
 }
 
@@ -600,15 +607,24 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase1_bf16_kernel(P
   wave_lo = __builtin_amdgcn_readfirstlane(wave_lo);   // wave-uniform
   reset_state(w);
 
+  // anchor rows (all visible: they precede the block or sit in their own
+  // buffer), then the block's own rows up to the workgroup's last token
   TileSeq seq;
-  seq.a_hi = i > 0 ? (int)g.a : 0;
-  seq.n_a = (seq.a_hi + TKEYS - 1) / TKEYS;
+  int64_t a_lo, a_hi;
+  const bool ext = anchor_range(g, a.anchor_mode, i, &a_lo, &a_hi);
+  seq.a_lo = (int)a_lo;
+  seq.a_hi = (int)a_hi;
+  seq.Ka = ext ? (const char*)a.Ka + ((size_t)beta * g.Hkv + kvh) * (size_t)g.a * ROWB : Kb;
+  seq.Va = ext ? (const char*)a.Va + ((size_t)beta * g.Hkv + kvh) * (size_t)g.a * ROWB : Vb;
+  seq.Kl = Kb;
+  seq.Vl = Vb;
+  seq.n_a = (seq.a_hi - seq.a_lo + TKEYS - 1) / TKEYS;
   seq.loc_lo = s;
   seq.loc_hi = wg_last;
   seq.n_tiles = seq.n_a + (wg_last - s + TKEYS - 1) / TKEYS;
 
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend<RB>(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
+  attend<RB>(w, seq, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
@@ -683,11 +699,12 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase2_rows_bf16_ker
   reset_state(w);
 
   TileSeq seq;
-  seq.a_hi = 0; seq.n_a = 0; seq.loc_lo = lo; seq.loc_hi = hi;
+  seq.a_lo = 0; seq.a_hi = 0; seq.n_a = 0; seq.loc_lo = lo; seq.loc_hi = hi;
+  seq.Ka = Kb; seq.Va = Vb; seq.Kl = Kb; seq.Vl = Vb;
   seq.n_tiles = hi > lo ? (hi - lo + TKEYS - 1) / TKEYS : 0;
 
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend<RB>(w, seq, Kb, Vb, row_lim, wave_lo, g.scale * LOG2E, lds0);
+  attend<RB>(w, seq, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {

@@ -150,7 +150,14 @@ __global__ __launch_bounds__(ROWS) void phase1_f32_kernel(Phase1Args a, int tile
               active, g.scale * LOG2E);
   int64_t limit = active ? p + 1 : 0;
   int64_t last = row0 + ROWS < e ? row0 + ROWS : e;   // exclusive bound of the tile's rows
-  if (i > 0) attend_range<D>(st, Kb, Vb, 0, g.a, limit, Ks, Vs);   // anchor: fully visible
+  int64_t a_lo, a_hi;                                              // anchor: fully visible
+  if (anchor_range(g, a.anchor_mode, i, &a_lo, &a_hi)) {
+    const float* Kab = (const float*)a.Ka + ((int64_t)beta * g.Hkv + kvh) * g.a * D;
+    const float* Vab = (const float*)a.Va + ((int64_t)beta * g.Hkv + kvh) * g.a * D;
+    attend_range<D>(st, Kab, Vab, a_lo, a_hi, limit, Ks, Vs);
+  } else {
+    attend_range<D>(st, Kb, Vb, a_lo, a_hi, limit, Ks, Vs);
+  }
   attend_range<D>(st, Kb, Vb, s, last, limit, Ks, Vs);             // own block, causal
   if (active) {
     float* o = (float*)a.O + (((int64_t)beta * g.L + p) * g.Hq + h) * D;

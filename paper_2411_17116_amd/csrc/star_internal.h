@@ -37,6 +37,10 @@ struct Geom {
   float scale;          // softmax scale (natural units)
 };
 
+// What prefixes a context block after the first (values of the public
+// STAR_ATTN_ANCHOR_* constants).
+enum AnchorMode { ANCHOR_FIRST = 0, ANCHOR_PREVIOUS = 1, ANCHOR_EXTERNAL = 2 };
+
 struct Phase1Args {
   Geom g;
   const void* Q;        // [B, L, Hq, d]
@@ -44,7 +48,20 @@ struct Phase1Args {
   float* LSE;           // [B, Hq, L] or null
   const void* Kc;       // caches [B, Hkv, cap, d], already holding the context
   const void* Vc;
+  int32_t anchor_mode;  // AnchorMode
+  const void* Ka;       // ANCHOR_EXTERNAL: anchor keys / values, head-major
+  const void* Va;       // [B, Hkv, a, d]; otherwise unused
 };
+
+// Anchor key rows [*lo, *hi) of 0-based block i, and whether they index the
+// external anchor buffers (true) or the caches (false).  Block 0 has none.
+__host__ __device__ inline bool anchor_range(const Geom& g, int mode, int64_t i, int64_t* lo,
+                                             int64_t* hi) {
+  if (i == 0 || g.a == 0) { *lo = 0; *hi = 0; return false; }
+  if (mode == ANCHOR_PREVIOUS) { *lo = i * g.b - g.a; *hi = i * g.b; return false; }
+  *lo = 0; *hi = g.a;
+  return mode == ANCHOR_EXTERNAL;
+}
 
 struct Phase2Args {
   Geom g;

@@ -16,7 +16,7 @@ HEADER = os.path.join(ROOT, "include", "star_attn.h")
 # status codes as the header defines them
 ERR = dict(INVALID_SHAPE=-1, NULL_POINTER=-2, UNSUPPORTED_HEAD_DIM=-3, UNSUPPORTED_DTYPE=-4,
            ANCHOR_GT_BLOCK=-5, CACHE_OVERFLOW=-6, WORKSPACE_TOO_SMALL=-7, LAUNCH_FAILED=-8,
-           MISALIGNED=-9)
+           MISALIGNED=-9, INVALID_MODE=-10)
 
 
 @pytest.fixture(scope="module")
@@ -39,7 +39,8 @@ def test_header_symbols_are_exported(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(star_attn_[a-z0-9_]+)\s*\(", text)
     assert set(names) >= {"star_attn_phase1", "star_attn_phase2", "star_attn_workspace_bytes",
-                          "star_attn_status_string", "star_attn_kernel_path"}
+                          "star_attn_status_string", "star_attn_kernel_path",
+                          "star_attn_phase1_anchor", "star_attn_phase1_workspace_bytes"}
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -66,6 +67,12 @@ def test_shape_struct_layout_matches_header():
 def _p1(lib, shape, Q=0x1000, K=0x1000, V=0x1000, O=0x1000, LSE=None, Kc=0x1000, Vc=0x1000):
     return lib.star_attn_phase1(ctypes.byref(shape) if shape is not None else None,
                                 Q, K, V, O, LSE, Kc, Vc, None, 0, None)
+
+
+def _p1a(lib, shape, mode, Q=0x1000, K=0x1000, V=0x1000, Ka=0x1000, Va=0x1000, O=0x1000, LSE=None,
+         Kc=0x1000, Vc=0x1000, ws=0x1000, ws_bytes=0):
+    return lib.star_attn_phase1_anchor(ctypes.byref(shape), mode, Q, K, V, Ka, Va, O, LSE, Kc, Vc,
+                                       ws, ws_bytes, None)
 
 
 def _p2(lib, shape, cache_len, q_len, Qq=0x1000, Kq=0x1000, Vq=0x1000, Kc=0x1000, Vc=0x1000,
@@ -149,3 +156,26 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
     with pytest.raises(FileNotFoundError):
         binding.load_library()
+
+
+def test_phase1_anchor_variant_arguments(lib):
+    shape = good_shape()
+    EXT = binding.ANCHOR_EXTERNAL
+    for mode in (-1, 3, 99):
+        assert _p1a(lib, shape, mode) == ERR["INVALID_MODE"]
+    assert _p1a(lib, good_shape(anchor=300), binding.ANCHOR_PREVIOUS) == ERR["ANCHOR_GT_BLOCK"]
+    for mode in (binding.ANCHOR_FIRST, binding.ANCHOR_PREVIOUS, EXT):
+        assert _p1a(lib, shape, mode, Q=None) == ERR["NULL_POINTER"]
+        assert _p1a(lib, shape, mode, Kc=0x1004) == ERR["MISALIGNED"]
+    # the external anchor needs its tensors and a workspace for their head-major copy
+    need = sa.binding.phase1_workspace_bytes(shape, EXT)
+    assert need == 2 * 1 * 2 * 256 * 128 * 2 and need % 256 == 0
+    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_FIRST) == 0
+    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_PREVIOUS) == 0
+    assert sa.binding.phase1_workspace_bytes(good_shape(batch=0), EXT) == 0
+    assert _p1a(lib, shape, EXT, Ka=None, ws_bytes=need) == ERR["NULL_POINTER"]
+    assert _p1a(lib, shape, EXT, Va=None, ws_bytes=need) == ERR["NULL_POINTER"]
+    assert _p1a(lib, shape, EXT, ws=None, ws_bytes=need) == ERR["NULL_POINTER"]
+    assert _p1a(lib, shape, EXT, Ka=0x1008, ws_bytes=need) == ERR["MISALIGNED"]
+    assert _p1a(lib, shape, EXT, ws=0x1010, ws_bytes=need) == ERR["MISALIGNED"]
+    assert _p1a(lib, shape, EXT, ws_bytes=need - 1) == ERR["WORKSPACE_TOO_SMALL"]

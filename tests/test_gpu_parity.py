@@ -40,7 +40,8 @@ def test_fp32_head_dim_128():
 @pytest.mark.parametrize("Hq,Hkv,L,b,a,lq,nd", [
     (4, 1, 2048, 512, 512, 40, 3),     # G = 4: four heads per workgroup
     (8, 1, 1500, 400, 100, 130, 2),    # G = 8, ragged everything, anchor < block
-    (2, 2, 1024, 256, 256, 64, 2),     # G = 1: one head, 128 tokens per workgroup
+    (2, 2, 1024, 256, 256, 64, 2),     # G = 1: one head per workgroup
+    (6, 2, 700, 256, 129, 20, 2),      # G = 3: odd group, one head per workgroup
     (6, 3, 900, 300, 0, 17, 2),        # G = 2, no anchor
     (4, 1, 700, 1024, 1024, 5, 4),     # single block (block > context)
 ])
