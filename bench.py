@@ -16,6 +16,10 @@ resident in HBM before the timed region.  Prints ONE JSON line:
   full_causal         the same kernels run with block = anchor = L (one block)
   cpu_baseline        the fp64 oracle timed on this host's cores on a bounded
                       sample of the same workload (a reported baseline only)
+  power               socket power and shader clock that `amd-smi` reports while
+                      phase 1 runs back to back for about two seconds (the MFMA
+                      peak assumes 2.4 GHz; under this load the chip runs at its
+                      power limit and clocks lower)
 
 All timings are HIP events recorded on the stream the kernels are launched on.
 """
@@ -25,8 +29,11 @@ import argparse
 import json
 import math
 import os
+import re
 import statistics
+import subprocess
 import sys
+import tempfile
 import time
 
 import torch
@@ -146,6 +153,102 @@ def cpu_baseline(cfg, inp, budget_s=12.0):
     }
 
 
+_POLLER = r"""
+import re, subprocess, sys, time
+out = open(sys.argv[1], "a", buffering=1)
+while True:
+    t = time.time()
+    try:
+        txt = subprocess.run(["amd-smi", "metric", "--power", "--clock"], capture_output=True,
+                             text=True, timeout=10).stdout
+    except Exception:
+        break
+    p = re.search(r"SOCKET_POWER:\s*(\d+)", txt)
+    c = re.search(r"GFX_0:\s*\n\s*CLK:\s*(\d+)", txt)
+    if not (p and c):
+        break
+    out.write("%.3f %.3f %s %s\n" % (t, time.time(), p.group(1), c.group(1)))
+    time.sleep(0.1)
+"""
+
+
+class PowerPoller:
+    """Polls `amd-smi metric --power --clock` from a child process that is started
+    before this process touches the GPU.  Samples are (t_begin, t_end, W, MHz)."""
+
+    def __init__(self):
+        self.proc = None
+        self.path = None
+
+    def start(self):
+        try:
+            fd, self.path = tempfile.mkstemp(prefix="star_power_", suffix=".txt")
+            os.close(fd)
+            self.proc = subprocess.Popen([sys.executable, "-c", _POLLER, self.path],
+                                         stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        except OSError:
+            self.proc = None
+
+    def stop(self):
+        if self.proc is not None:
+            self.proc.terminate()
+            try:
+                self.proc.wait(timeout=15)
+            except subprocess.TimeoutExpired:
+                self.proc.kill()
+            self.proc = None
+
+    def window(self, t0, t1):
+        """Samples taken entirely inside [t0, t1]."""
+        rows = []
+        try:
+            with open(self.path) as f:
+                for line in f:
+                    a, b, w, mhz = line.split()
+                    if float(a) >= t0 and float(b) <= t1:
+                        rows.append((float(w), float(mhz)))
+        except (OSError, ValueError, TypeError):
+            pass
+        return rows
+
+    def cleanup(self):
+        self.stop()
+        if self.path:
+            try:
+                os.unlink(self.path)
+            except OSError:
+                pass
+
+
+def sustained_phase1(cfg, shape, inp, bufs, poller, seconds=2.0):
+    """Phase 1 back to back for about `seconds`, with the power / clock samples
+    that fall inside that window."""
+    t = Timer()
+    e = t.start()
+    sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+    i = t.stop(e)
+    torch.cuda.synchronize()
+    n = max(3, int(seconds * 1e3 / max(t.ms(i), 1e-3)))
+    t0 = time.time()
+    e = t.start()
+    for _ in range(n):
+        sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+    i = t.stop(e)
+    torch.cuda.synchronize()
+    t1 = time.time()
+    ms = t.ms(i) / n
+    rows = poller.window(t0 + 0.3, t1) if poller is not None else []   # skip the ramp
+    res = {"phase1_calls": n, "phase1_ms": ms,
+           "phase1_tflops": phase1_flops(cfg) / (ms * 1e-3) / 1e12,
+           "source": "amd-smi metric --power --clock, polled while phase 1 runs back to back",
+           "samples": len(rows)}
+    if rows:
+        res["socket_power_w"] = statistics.median(r[0] for r in rows)
+        res["gfx_clock_mhz"] = statistics.median(r[1] for r in rows)
+        res["mfma_peak_at_clock_tflops"] = MFMA_PEAK_TFLOPS.get(cfg.dtype, 0.0) * res["gfx_clock_mhz"] / 2400.0
+    return res
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summaries
     (profiles/traffic.json), or None if that kernel/workload was not profiled."""
@@ -165,6 +268,8 @@ def main():
     ap.add_argument("--config", default="C3", choices=sorted(workloads.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-causal", action="store_true")
+    ap.add_argument("--no-power", action="store_true",
+                    help="skip the sustained phase-1 run with power / clock polling")
     ap.add_argument("--calib-copy", action="store_true",
                     help="profiling aid: also run one device copy of the K cache (known size) "
                          "so that HBM byte counters can be scaled")
@@ -175,8 +280,14 @@ def main():
         print("bench.py: this build measures one GPU only (the hot path of one GPU's share); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    poller = None
+    if not args.no_power:
+        poller = PowerPoller()
+        poller.start()           # before this process initialises the GPU
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
+        if poller:
+            poller.cleanup()
         sys.exit(1)
     sa.load_library()          # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
@@ -271,6 +382,10 @@ def main():
         out["full_causal"] = {"ms": f_ms, "tflops": f_flops / (f_ms * 1e-3) / 1e12,
                               "time_ratio_vs_star": f_ms / p1_ms,
                               "flop_ratio_vs_star": f_flops / flops}
+    if poller is not None:
+        if "phase1" in sections:
+            out["power"] = sustained_phase1(cfg, shape, inp, bufs, poller)
+        poller.cleanup()
     out["paper_context"] = ("paper reports only whole-model speedups vs Ring Attention on 8-32 "
                             "A100 (e.g. 2.7x at 128K, Llama-3.1-8B, block 32K); no operator-level "
                             "number exists, so vs_baseline is null")
