@@ -164,17 +164,17 @@ while True:
     except Exception:
         break
     p = re.search(r"SOCKET_POWER:\s*(\d+)", txt)
-    c = re.search(r"GFX_0:\s*\n\s*CLK:\s*(\d+)", txt)
+    c = [int(x) for x in re.findall(r"GFX_\d+:\s*\n\s*CLK:\s*(\d+)", txt)]
     if not (p and c):
         break
-    out.write("%.3f %.3f %s %s\n" % (t, time.time(), p.group(1), c.group(1)))
+    out.write("%.3f %.3f %s %.1f\n" % (t, time.time(), p.group(1), sum(c) / len(c)))
     time.sleep(0.1)
 """
 
 
 class PowerPoller:
     """Polls `amd-smi metric --power --clock` from a child process that is started
-    before this process touches the GPU.  Samples are (t_begin, t_end, W, MHz)."""
+    before this process touches the GPU.  Samples are (t_begin, t_end, socket W, shader MHz averaged over the XCDs)."""
 
     def __init__(self):
         self.proc = None
