@@ -10,7 +10,8 @@ resident in HBM before the timed region.  Prints ONE JSON line:
 
   value / unit        phase-1 context tokens per second (B * L / phase-1 time)
   ms_per_step         wall time of the whole step (phase 1 + query + all decodes)
-  phase2              decode microseconds per step and query-encode milliseconds
+  phase2              decode microseconds per step and query-encode milliseconds;
+                      decode_graph = the same decode calls replayed from one HIP graph
   roofline            phase-1 attention: achieved bf16 TFLOP/s vs. 2.5 PFLOP/s dense
   roofline_decode     decode step: algorithmic KV bytes / step time vs. 8 TB/s
   full_causal         the same kernels run with block = anchor = L (one block)
@@ -249,6 +250,42 @@ def sustained_phase1(cfg, shape, inp, bufs, poller, seconds=2.0):
     return res
 
 
+def decode_graph(cfg, shape, bufs, reps=5):
+    """All decode steps of the configuration captured into one HIP graph and
+    replayed: microseconds per step without per-launch host work."""
+    side = torch.cuda.Stream()
+
+    def steps():
+        cache_len = cfg.L + cfg.lq
+        for t in range(cfg.nd):
+            sa.phase2(shape, cache_len, bufs["Qd"][t], bufs["Kd"][t], bufs["Vd"][t], bufs["Kc"],
+                      bufs["Vc"], bufs["Od"][t], bufs["ws"])
+            cache_len += 1
+
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        steps()
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        steps()
+    graph.replay()
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(reps):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e3 / cfg.nd)
+    us = statistics.median(times)
+    gbs = decode_bytes(cfg, cfg.L + cfg.lq + cfg.nd // 2) / (us * 1e-6) / 1e9
+    return {"us_per_step": us, "gb_per_s": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+            "note": f"{cfg.nd} decode calls captured into one HIP graph, median of {reps} replays"}
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summaries
     (profiles/traffic.json), or None if that kernel/workload was not profiled."""
@@ -268,6 +305,8 @@ def main():
     ap.add_argument("--config", default="C3", choices=sorted(workloads.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-causal", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the HIP-graph replay of the decode loop")
     ap.add_argument("--no-power", action="store_true",
                     help="skip the sustained phase-1 run with power / clock polling")
     ap.add_argument("--calib-copy", action="store_true",
@@ -382,6 +421,8 @@ def main():
         out["full_causal"] = {"ms": f_ms, "tflops": f_flops / (f_ms * 1e-3) / 1e12,
                               "time_ratio_vs_star": f_ms / p1_ms,
                               "flop_ratio_vs_star": f_flops / flops}
+    if "decode" in sections and cfg.nd and not args.no_graph:
+        out["phase2"]["decode_graph"] = decode_graph(cfg, shape, bufs)
     if poller is not None:
         if "phase1" in sections:
             out["power"] = sustained_phase1(cfg, shape, inp, bufs, poller)
