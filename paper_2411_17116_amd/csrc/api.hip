@@ -98,11 +98,15 @@ static bool make_plan(const star_attn_shape* s, int64_t q_len, int64_t total, bo
       int hpw = heads_per_workgroup(g.G, flash_row_blocks());
       wgs = (int64_t)g.B * g.Hkv * (g.G / hpw) * ceil_div(q_len, 32 * flash_row_blocks() / hpw);
     }
-    int64_t spb = ceil_div(1024, wgs * n);
-    int64_t spb_max = bmax / 256 > 1 ? bmax / 256 : 1;
+    // one thread walks a whole split in the fp32 kernel, so short calls are cut
+    // much finer there (down to one 32-key LDS tile per split)
+    const int64_t min_len = s->dtype == STAR_ATTN_F32 ? 32 : 256;
+    const int64_t want_wgs = s->dtype == STAR_ATTN_F32 ? 4096 : 1024;
+    int64_t spb = ceil_div(want_wgs, wgs * n);
+    int64_t spb_max = bmax / min_len > 1 ? bmax / min_len : 1;
     if (spb > spb_max) spb = spb_max;
     if (spb < 1) spb = 1;
-    split_len = round_up(ceil_div(bmax, spb), 64);
+    split_len = round_up(ceil_div(bmax, spb), s->dtype == STAR_ATTN_F32 ? 32 : 64);
   }
   int64_t spb = ceil_div(bmax, split_len);
   int64_t st = tail_cap > 0 ? ceil_div(tail_cap, split_len) : 1;

@@ -4,9 +4,12 @@
 //
 // A decode step reads every cached K and V byte exactly once and does 4-8 flops
 // per byte, so the kernel is built as an HBM stream:
-//   * one wavefront per workgroup, one split (a contiguous run of keys of one
-//     KV head) per workgroup, no barriers; the host sizes the splits so that
-//     every resident workgroup slot gets one equal split;
+//   * one wavefront per workgroup, one split (a set of keys of one KV head) per
+//     workgroup, no barriers; without per-part outputs there is one split per
+//     resident workgroup slot and split s is the comb of 32-key steps
+//     s, s + S, s + 2S, ... so that at any moment the S wavefronts of a KV head
+//     read one contiguous window of its cache (every memory channel busy, none
+//     hot); with per-part outputs a split is a contiguous run inside one part;
 //   * the wavefront DMAs 32-key steps of K and V (8 KiB each) straight into a
 //     four-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
 //     bursts, no VGPRs held by data in flight -- and waits with partial vmcnt so
@@ -203,11 +206,24 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
 
   const int cache_len = (int)a.cache_len;
   const int total = cache_len + a.q_len;
-  int64_t lo64, hi64;
-  split_range(a.plan, g.L, g.b, total, sp, &lo64, &hi64);
-  const int lo = (int)lo64, hi = (int)hi64;
+  // step `cur` of this split covers keys [base + cur * stride, +32) below hi
+  int base, stride, nsteps, hi;
+  if (a.plan.flat) {
+    const int S = a.plan.s_total, T = (total + STEP - 1) / STEP;
+    base = sp * STEP;
+    stride = S * STEP;
+    nsteps = sp < T ? (T - sp + S - 1) / S : 0;
+    hi = total;
+  } else {
+    int64_t lo64, hi64;
+    split_range(a.plan, g.L, g.b, total, sp, &lo64, &hi64);
+    base = (int)lo64;
+    stride = STEP;
+    hi = (int)hi64;
+    nsteps = hi > base ? (hi - base + STEP - 1) / STEP : 0;
+  }
   size_t r = (((size_t)beta * a.plan.s_total + sp) * g.Hq + head) * a.q_len + j;
-  if (lo >= hi) {                              // empty split (short block, unused tail)
+  if (nsteps == 0) {                           // empty split (short block, unused tail)
     if (live && j4 == 0) a.LSE_sub[r] = -INFINITY;
     return;
   }
@@ -220,35 +236,35 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   src.cache_len = cache_len;
   src.new_stride = g.Hkv * ROWB;
 
-  // Algorithm 2, append: the new tokens whose rows fall into this split join the
-  // cache (16 lanes move one 256-byte row of K and of V).
+  // Algorithm 2, append: the new tokens whose rows fall into this split's steps
+  // join the cache (16 lanes move one 256-byte row of K and of V).
   if (hi > cache_len) {
-    int first = lo > cache_len ? lo : cache_len;
-    for (int key = first + (lane >> 4); key < hi; key += 4) {
+    for (int key = cache_len + (lane >> 4); key < hi; key += 4) {
+      const int rel = key - base;
+      if (rel < 0 || (rel % stride) >= STEP) continue;      // another split's step
       size_t so = (size_t)(key - cache_len) * src.new_stride + (lane & 15) * 16;
       size_t dof = (size_t)key * ROWB + (lane & 15) * 16;
       *(i32x4*)(const_cast<char*>(src.Kb) + dof) = *(const i32x4*)(src.Kn + so);
       *(i32x4*)(const_cast<char*>(src.Vb) + dof) = *(const i32x4*)(src.Vn + so);
     }
+
+    // the stores are complete before DMAs are counted
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
+  // The query loads are issued here and consumed after the first step's wait:
+  // their latency overlaps the first DMAs instead of preceding them.
   DecState w;
   {
     const char* qrow = (const char*)a.Qq + (((size_t)beta * a.q_len + (live ? j : 0)) * g.Hq +
                                             (live ? head : kvh * g.G)) * ROWB;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      bf16x8 v = *(const bf16x8*)(qrow + (32 * t + 8 * j4) * 2);
-      if (!live) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-      w.q[t] = v;
-    }
+    for (int t = 0; t < 4; ++t) w.q[t] = *(const bf16x8*)(qrow + (32 * t + 8 * j4) * 2);
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) w.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     w.m = -INFINITY;
     w.l = 0.f;
   }
-  // everything this wave loaded or stored so far is complete before DMAs are counted
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   const unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
   // K operand: lane (i = lane%16, j4) reads row i, chunk 4t + j4
@@ -277,26 +293,34 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   const int lim = row_lim < hi ? row_lim : hi;
   const int free_hi = cache_len + 1 < hi ? cache_len + 1 : hi;
 
-  const int nsteps = (hi - lo + STEP - 1) / STEP;
   // ring slot of step s is s % RING; AHEAD = RING - 1 steps are in flight while
   // one is consumed
   constexpr int AHEAD = RING - 1;
   static_assert(RING >= 2 && RING <= 4, "vmcnt holds at most 63 outstanding DMAs");
 #pragma unroll
   for (int i = 0; i < AHEAD; ++i)
-    if (i < nsteps) issue_step(src, lo + i * STEP, hi, lds0 + i * 2 * STEPB, lane, voff);
+    if (i < nsteps) issue_step(src, base + i * stride, hi, lds0 + i * 2 * STEPB, lane, voff);
   for (int s = 0; s < nsteps; s += RING) {
 #pragma unroll
     for (int u = 0; u < RING; ++u) {
       const int cur = s + u;
       if (cur >= nsteps) break;
-      const int key0 = lo + cur * STEP;
+      const int key0 = base + cur * stride;
       // the slot that held step cur-1 is free: every LDS read of it has returned
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       if (cur + AHEAD < nsteps)
-        issue_step(src, key0 + AHEAD * STEP, hi, lds0 + ((u + AHEAD) % RING) * 2 * STEPB, lane, voff);
+        issue_step(src, key0 + AHEAD * stride, hi, lds0 + ((u + AHEAD) % RING) * 2 * STEPB, lane, voff);
       int later = nsteps - 1 - cur;
       wait_steps(later < AHEAD ? later : AHEAD);
+      if (cur == 0) {
+        // first use of the query: the loads were issued before every DMA, so the
+        // wait above covers them; dead columns contribute zeros
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          asm volatile("" : "+v"(w.q[t]));
+          if (!live) w.q[t] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+      }
       const bool masked = key0 + STEP > free_hi;
       if (u == 0) compute_step<0>(w, kaddr, vaddr, key0, lim, masked, c, j4);
       else if (u == 1) compute_step<1>(w, kaddr, vaddr, key0, lim, masked, c, j4);

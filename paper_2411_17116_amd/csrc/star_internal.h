@@ -16,10 +16,11 @@ namespace star {
 // indices from n_blocks * spb on are pieces of the tail.
 // ---------------------------------------------------------------------------
 //
-// A "flat" plan ignores part boundaries: split s is simply keys
-// [s * split_len, (s + 1) * split_len) of everything the call may see.  It is
-// used by decode-sized calls that do not ask for per-part outputs, where equal
-// splits (one per resident workgroup) matter more than part boundaries.
+// A "flat" plan ignores part boundaries: with S = s_total splits, split s is the
+// comb of 32-key steps s, s + S, s + 2S, ... of everything the call may see
+// (split_len only sizes S).  It is used by decode-sized calls that do not ask
+// for per-part outputs, where equal splits (one per resident workgroup) that
+// sweep the cache together matter more than part boundaries.
 struct SplitPlan {
   int64_t split_len;   // keys per split (multiple of 32)
   int32_t spb;         // splits per context block
@@ -89,16 +90,12 @@ struct MergeArgs {
   void* O;              // [B, q_len, Hq, d]
 };
 
-// Key range [lo, hi) of split s (hi clipped to what exists for this call).
+// Key range [lo, hi) of split s of a plan that is not flat (hi clipped to what
+// exists for this call).
 __host__ __device__ inline void split_range(const SplitPlan& p, int64_t L, int64_t b,
                                             int64_t total_keys, int s, int64_t* lo, int64_t* hi) {
   int n_ctx = p.n_blocks * p.spb;
-  if (p.flat) {
-    int64_t x = (int64_t)s * p.split_len;
-    int64_t y = x + p.split_len;
-    *lo = x < total_keys ? x : total_keys;
-    *hi = y < total_keys ? y : total_keys;
-  } else if (s < n_ctx) {
+  if (s < n_ctx) {
     int64_t m = s / p.spb, piece = s % p.spb;
     int64_t blo = m * b, bhi = (m + 1) * b < L ? (m + 1) * b : L;
     int64_t x = blo + piece * p.split_len;
