@@ -4,11 +4,11 @@
 // attention and log-sum-exp of a row tile over one split of the cache).
 //
 // Shape of the computation
-//   * A workgroup is 4 wavefronts; each wavefront owns 32 query rows and the
-//     whole head dimension.  The rows of a workgroup are GQA-packed: up to 4
-//     query heads of one KV group x 32 tokens, so the K/V tiles a workgroup
-//     streams are shared by all of its rows and every wavefront has the same
-//     causal frontier.
+//   * A workgroup is 8 wavefronts (two per SIMD, one workgroup per CU); each
+//     wavefront owns 32 query rows and the whole head dimension.  The rows of a
+//     workgroup are GQA-packed: up to 8 query heads of one KV group times 32 to
+//     256 tokens, so the K/V tiles a workgroup streams are fetched from L2 once
+//     per 256 rows, and the wavefronts' causal frontiers lie within those tokens.
 //   * K/V tiles of 64 keys are DMA'd from HBM/L2 straight into LDS
 //     (global_load_lds_dwordx4, no VGPR staging), double-buffered, one barrier
 //     per tile.  Inside a 256-byte key row the sixteen 16-byte chunks are
@@ -22,11 +22,12 @@
 //     exponentiated tile is already laid out as the B operand of the second
 //     MFMA: O^T += V^T P^T, with V^T fragments produced by the LDS transposing
 //     read.  P never touches LDS.
-//   * Softmax runs in the log2 domain in fp32 against a lazily raised reference
-//     maximum: the common path is one fma + one exp per score, a packed bf16
-//     conversion and a dot2 for the row sum; the row maximum is only searched
-//     (and the accumulators rescaled) for the first unit and when a row sum shows
-//     that the reference has become stale.  O / l does not depend on the reference.
+//   * Softmax runs in the log2 domain in fp32 against a reference maximum taken
+//     from the row's first 32 keys: the common path is one fma + one exp per
+//     score, a packed bf16 conversion and a dot2 for the row sum, with no
+//     maximum search and no rescale (O / l does not depend on the reference).
+//     If a row sum shows that the reference was too low to be safe, the
+//     workgroup redoes its rows with the exact online softmax.
 //   * The key loop is software-pipelined per 32-key unit: the QK MFMAs of unit
 //     u+1, the exponentials of unit u and the PV MFMAs of unit u-1 share one
 //     scheduling region whose order is pinned with sched_group_barrier.
@@ -418,7 +419,7 @@ __device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, 
   }
 }
 
-// Walk a tile sequence once for the calling wavefront (all four wavefronts of
+// Walk a tile sequence once for the calling wavefront (all wavefronts of
 // the workgroup call this with the same sequence).
 //   row_lim     this lane's exclusive causal key bound per row block (0 = inactive row)
 //   wave_lo     smallest row_lim among the wavefront's active rows: key tiles that
