@@ -130,6 +130,72 @@ def phase1_full(Q, K, V, b: int, a: int, scale: Optional[float] = None
     return O, LSE
 
 
+# --------------------------------------------------------------------------
+# Rotary position embedding (the position encoding of the Llama models the paper
+# evaluates; Section 2.1 fixes which position each token carries: a context
+# token keeps its index in the context, and the anchor keeps 0..a-1 -- so the
+# rotated key of an anchor token IS the rotated key of that context token and
+# one K tensor serves both roles.  Phase 2: the j-th new token of a call made
+# with `cache_len` cached tokens sits at position cache_len + j.)
+# --------------------------------------------------------------------------
+
+def rope_rotate(X, positions, theta: float) -> np.ndarray:
+    """Rotary embedding of X [..., T, H, d] at integer `positions` [T] with
+    base `theta`, in the half-split pairing of the Llama family: dimension i
+    (i < d/2) pairs with dimension i + d/2, and the pair is turned by the angle
+    pos * theta^(-2i/d):
+        y_i       = x_i cos - x_(i+d/2) sin
+        y_(i+d/2) = x_(i+d/2) cos + x_i sin."""
+    X = np.asarray(X, F64)
+    d = X.shape[-1]
+    if d % 2:
+        raise ValueError("head_dim must be even")
+    half = d // 2
+    inv_freq = np.asarray([float(theta) ** (-2.0 * i / d) for i in range(half)], F64)
+    ang = np.asarray(positions, F64)[:, None] * inv_freq[None, :]        # [T, d/2]
+    cos = np.cos(ang)[:, None, :]                                        # [T, 1, d/2]
+    sin = np.sin(ang)[:, None, :]
+    lo, hi = X[..., :half], X[..., half:]
+    return np.concatenate([lo * cos - hi * sin, hi * cos + lo * sin], axis=-1)
+
+
+def phase1_rope_rows(Q, K, V, triples, b: int, a: int, theta: float, pos0: int = 0,
+                     scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Phase 1 on projections that have not been rotated yet: context token t
+    is rotated at position pos0 + t, then the method runs unchanged.  Only the
+    rows the triples need are rotated (row by row, as `phase1_row` walks them)."""
+    triples = list(triples)
+    B, L, Hq, d = Q.shape
+    Hkv = K.shape[2]
+    O = np.zeros((len(triples), V.shape[3]), F64)
+    LSE = np.zeros(len(triples), F64)
+    sc = softmax_scale(d, scale)
+    for t, (beta, h, p) in enumerate(triples):
+        g = h // (Hq // Hkv)
+        ks = visible_keys(p, L, b, a)
+        q = rope_rotate(np.asarray(Q[beta, p, h], F64)[None, None, :], [pos0 + p], theta)[0, 0]
+        Kr = rope_rotate(np.asarray(K[beta, ks, g], F64)[:, None, :], pos0 + ks, theta)[:, 0]
+        O[t], LSE[t] = attend(q, Kr, V[beta, ks, g], sc)
+    return O, LSE
+
+
+def kv_cache_rope(K, V, capacity: int, theta: float, pos0: int = 0):
+    """The cache phase 1 leaves behind when it is handed unrotated keys: every
+    context token once, its key rotated at its own position (float64)."""
+    B, L, Hkv, d = K.shape
+    Kr = rope_rotate(np.asarray(K, F64), pos0 + np.arange(L), theta)     # [B, L, Hkv, d]
+    return kv_cache(Kr, np.asarray(V, F64), capacity)
+
+
+def phase2_rope_inputs(Qn, Kn, cache_len: int, theta: float, pos0: int = 0):
+    """Rotate the unrotated projections of a phase-2 call: its j-th new token
+    sits at position pos0 + cache_len + j.  Returns (Q, K) in float64, to be
+    appended / attended exactly like already-rotated inputs."""
+    q_len = Qn.shape[1]
+    pos = pos0 + cache_len + np.arange(q_len)
+    return rope_rotate(np.asarray(Qn, F64), pos, theta), rope_rotate(np.asarray(Kn, F64), pos, theta)
+
+
 # Anchor variants of the ablation study (Section 4.1, "Position and Content of
 # Anchor Block"; Section 4.2 for the anchor size).  Block 1 is plain causal
 # attention in every variant; the variants differ in what prefixes a later block.
