@@ -179,6 +179,52 @@ int star_attn_phase2(const star_attn_shape* shape,
                      void* O,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Unrotated projections: rotary position embedding applied inside the calls.
+ *
+ * Section 2.1 fixes the position every token carries: context token t sits at
+ * pos0 + t (the anchor therefore keeps positions pos0 .. pos0 + a - 1, and the
+ * rotated key of an anchor token is the rotated key of that context token, so
+ * one rotated K serves both roles); the j-th new token of a phase-2 call sits
+ * at pos0 + cache_len + j.  The embedding is the one of the Llama family the
+ * paper evaluates: dimension i < d/2 pairs with dimension i + d/2 and the pair
+ * is turned by the angle pos * rope_theta^(-2i/d)
+ *     y_i = x_i cos - x_(i+d/2) sin,   y_(i+d/2) = x_(i+d/2) cos + x_i sin.
+ * Angles are evaluated in double precision; the rotation runs in fp32 and the
+ * result is rounded once to the storage dtype.
+ *
+ * star_attn_phase1_rope / star_attn_phase2_rope are star_attn_phase1 /
+ * star_attn_phase2 on unrotated Q and K:
+ *   Q, Qq   in/out  rotated IN PLACE (on return they hold the rotated queries)
+ *   K, Kq   in      unrotated; they are rotated on their way into K_cache, so
+ *                   the cache holds rotated keys (what later calls attend to)
+ *   rope_theta      base of the frequencies, > 1 (e.g. 10000, 500000)
+ *   pos0            position of context token 0, >= 0
+ * Every other argument, the outputs and the error codes are those of the plain
+ * entry points; a rope_theta or pos0 out of range is STAR_ATTN_ERR_INVALID_SHAPE.
+ *
+ * star_attn_rope is the rotation alone: X [B, n_tokens, n_heads, d] -> Y (same
+ * layout; Y may be X), token t at pos0 + t; B, d and dtype come from `shape`.
+ * With it a caller can build the separately rotated anchor of the position-id
+ * ablations (Section 4.1) for STAR_ATTN_ANCHOR_EXTERNAL.
+ */
+int star_attn_phase1_rope(const star_attn_shape* shape, double rope_theta, int64_t pos0,
+                          void* Q, const void* K, const void* V,
+                          void* O_ctx, float* LSE_ctx,
+                          void* K_cache, void* V_cache,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+int star_attn_phase2_rope(const star_attn_shape* shape, double rope_theta, int64_t pos0,
+                          int64_t cache_len, int64_t q_len,
+                          void* Qq, const void* Kq, const void* Vq,
+                          void* K_cache, void* V_cache,
+                          float* O_part, float* LSE_part,
+                          void* O,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+int star_attn_rope(const star_attn_shape* shape, int32_t n_heads, int64_t n_tokens, int64_t pos0,
+                   double rope_theta, const void* X, void* Y, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code (host memory, never freed). */
 const char* star_attn_status_string(int status);
 

@@ -160,10 +160,16 @@ def rope_rotate(X, positions, theta: float) -> np.ndarray:
 
 
 def phase1_rope_rows(Q, K, V, triples, b: int, a: int, theta: float, pos0: int = 0,
-                     scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+                     scale: Optional[float] = None, storage=None
+                     ) -> Tuple[np.ndarray, np.ndarray]:
     """Phase 1 on projections that have not been rotated yet: context token t
     is rotated at position pos0 + t, then the method runs unchanged.  Only the
-    rows the triples need are rotated (row by row, as `phase1_row` walks them)."""
+    rows the triples need are rotated (row by row, as `phase1_row` walks them).
+
+    `storage`, if given, maps a float64 array to the values a storage format
+    can hold (e.g. round to bf16): the operator hands the rotated queries back
+    and keeps the rotated keys in its cache in that format, and attention is
+    defined on what is stored."""
     triples = list(triples)
     B, L, Hq, d = Q.shape
     Hkv = K.shape[2]
@@ -175,6 +181,8 @@ def phase1_rope_rows(Q, K, V, triples, b: int, a: int, theta: float, pos0: int =
         ks = visible_keys(p, L, b, a)
         q = rope_rotate(np.asarray(Q[beta, p, h], F64)[None, None, :], [pos0 + p], theta)[0, 0]
         Kr = rope_rotate(np.asarray(K[beta, ks, g], F64)[:, None, :], pos0 + ks, theta)[:, 0]
+        if storage is not None:
+            q, Kr = storage(q), storage(Kr)
         O[t], LSE[t] = attend(q, Kr, V[beta, ks, g], sc)
     return O, LSE
 

@@ -71,6 +71,14 @@ def load_library():
                                             vp, sz, vp]
     lib.star_attn_phase1_workspace_bytes.restype = sz
     lib.star_attn_phase1_workspace_bytes.argtypes = [P, ctypes.c_int]
+    dbl = ctypes.c_double
+    lib.star_attn_phase1_rope.restype = ctypes.c_int
+    lib.star_attn_phase1_rope.argtypes = [P, dbl, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.star_attn_phase2_rope.restype = ctypes.c_int
+    lib.star_attn_phase2_rope.argtypes = [P, dbl, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                          sz, vp]
+    lib.star_attn_rope.restype = ctypes.c_int
+    lib.star_attn_rope.argtypes = [P, ctypes.c_int32, i64, i64, dbl, vp, vp, vp]
     lib.star_attn_phase2.restype = ctypes.c_int
     lib.star_attn_phase2.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.star_attn_status_string.restype = ctypes.c_char_p
@@ -149,6 +157,35 @@ def phase1_anchor(shape: StarShape, anchor_mode: int, Q, K, V, O_ctx, K_cache, V
         ctypes.byref(shape), int(anchor_mode), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_anchor),
         _ptr(V_anchor), _ptr(O_ctx), _ptr(LSE_ctx), _ptr(K_cache), _ptr(V_cache),
         _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)
+
+
+def phase1_rope(shape: StarShape, rope_theta: float, Q, K, V, O_ctx, K_cache, V_cache, pos0=0,
+                LSE_ctx=None, stream=None) -> None:
+    """star_attn_phase1_rope: phase 1 on unrotated Q (rotated in place) and K."""
+    rc = load_library().star_attn_phase1_rope(
+        ctypes.byref(shape), float(rope_theta), int(pos0), _ptr(Q), _ptr(K), _ptr(V), _ptr(O_ctx),
+        _ptr(LSE_ctx), _ptr(K_cache), _ptr(V_cache), None, 0, _stream(stream))
+    _check(rc)
+
+
+def phase2_rope(shape: StarShape, rope_theta: float, cache_len: int, Qq, Kq, Vq, K_cache, V_cache,
+                O, workspace, pos0=0, O_part=None, LSE_part=None, stream=None) -> None:
+    """star_attn_phase2_rope: phase 2 on unrotated Qq (rotated in place) and Kq."""
+    q_len = Qq.shape[1]
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load_library().star_attn_phase2_rope(
+        ctypes.byref(shape), float(rope_theta), int(pos0), int(cache_len), int(q_len), _ptr(Qq),
+        _ptr(Kq), _ptr(Vq), _ptr(K_cache), _ptr(V_cache), _ptr(O_part), _ptr(LSE_part), _ptr(O),
+        _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)
+
+
+def rope(shape: StarShape, X, Y, rope_theta: float, pos0=0, stream=None) -> None:
+    """star_attn_rope: rotate X [B, T, H, d] into Y (may be X), token t at pos0 + t."""
+    rc = load_library().star_attn_rope(ctypes.byref(shape), int(X.shape[2]), int(X.shape[1]),
+                                       int(pos0), float(rope_theta), _ptr(X), _ptr(Y),
+                                       _stream(stream))
     _check(rc)
 
 

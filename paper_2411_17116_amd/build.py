@@ -13,8 +13,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstarattn.so")
-SOURCES = ["api.hip", "kv_cache.hip", "flash_f32.hip", "flash_bf16.hip", "decode_bf16.hip",
-           "merge.hip"]
+SOURCES = ["api.hip", "kv_cache.hip", "rope.hip", "flash_f32.hip", "flash_bf16.hip",
+           "decode_bf16.hip", "merge.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -127,6 +127,19 @@ static size_t plan_bytes(const star_attn_shape* s, const SplitPlan& p, int64_t q
 
 static bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// Rotary embedding requested by the *_rope entry points (theta == 0: none).
+struct Rope {
+  double theta;
+  int64_t pos0;
+};
+
+static int validate_rope(const star_attn_shape* s, double theta, int64_t pos0) {
+  if (!(theta > 1.0) || isinf(theta) || pos0 < 0 || pos0 > ((int64_t)1 << 40))
+    return STAR_ATTN_ERR_INVALID_SHAPE;
+  (void)s;    // every supported head_dim is even
+  return STAR_ATTN_OK;
+}
+
 // Bytes of one head-major copy of the external anchor (K or V), 256-byte padded.
 static size_t anchor_copy_bytes(const star_attn_shape* s) {
   size_t es = s->dtype == STAR_ATTN_F32 ? 4 : 2;
@@ -171,13 +184,17 @@ size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor
   return anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ? 2 * anchor_copy_bytes(shape) : 0;
 }
 
-int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode, const void* Q,
-                            const void* K, const void* V, const void* K_anchor,
-                            const void* V_anchor, void* O_ctx, float* LSE_ctx, void* K_cache,
-                            void* V_cache, void* workspace, size_t workspace_bytes,
-                            void* hip_stream) {
+}  // extern "C"
+
+// Phase 1 behind every public variant.  With `rope`, Q is rotated in place and K
+// on its way into the cache.
+static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope* rope, void* Q,
+                       const void* K, const void* V, const void* K_anchor, const void* V_anchor,
+                       void* O_ctx, float* LSE_ctx, void* K_cache, void* V_cache, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
   int rc = validate_shape(shape);
   if (rc != STAR_ATTN_OK) return rc;
+  if (rope && (rc = validate_rope(shape, rope->theta, rope->pos0)) != STAR_ATTN_OK) return rc;
   if (anchor_mode != STAR_ATTN_ANCHOR_FIRST && anchor_mode != STAR_ATTN_ANCHOR_PREVIOUS &&
       anchor_mode != STAR_ATTN_ANCHOR_EXTERNAL)
     return STAR_ATTN_ERR_INVALID_MODE;
@@ -195,8 +212,16 @@ int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode, const
   Geom g = make_geom(shape);
   hipStream_t st = (hipStream_t)hip_stream;
   // Algorithm 1: keep the K/V of every block once (anchor copies never exist here).
-  if (launch_cache_write(g, shape->dtype, K, V, K_cache, V_cache, g.L, 0, st) != hipSuccess)
+  if (rope) {
+    if (launch_rope_rotate(shape->dtype, g.B, g.L, g.Hq, g.d, rope->pos0, rope->theta, Q, Q, st) !=
+            hipSuccess ||
+        launch_rope_cache_write(g, shape->dtype, K, K_cache, g.L, 0, rope->pos0, rope->theta, st) !=
+            hipSuccess ||
+        launch_cache_write(g, shape->dtype, nullptr, V, K_cache, V_cache, g.L, 0, st) != hipSuccess)
+      return STAR_ATTN_ERR_LAUNCH_FAILED;
+  } else if (launch_cache_write(g, shape->dtype, K, V, K_cache, V_cache, g.L, 0, st) != hipSuccess) {
     return STAR_ATTN_ERR_LAUNCH_FAILED;
+  }
   Phase1Args a;
   a.g = g; a.Q = Q; a.O = O_ctx; a.LSE = LSE_ctx; a.Kc = K_cache; a.Vc = V_cache;
   a.anchor_mode = anchor_mode; a.Ka = nullptr; a.Va = nullptr;
@@ -214,20 +239,59 @@ int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode, const
   return e == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
 }
 
+extern "C" {
+
+int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode, const void* Q,
+                            const void* K, const void* V, const void* K_anchor,
+                            const void* V_anchor, void* O_ctx, float* LSE_ctx, void* K_cache,
+                            void* V_cache, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  return phase1_impl(shape, anchor_mode, nullptr, const_cast<void*>(Q), K, V, K_anchor, V_anchor,
+                     O_ctx, LSE_ctx, K_cache, V_cache, workspace, workspace_bytes, hip_stream);
+}
+
 int star_attn_phase1(const star_attn_shape* shape, const void* Q, const void* K, const void* V,
                      void* O_ctx, float* LSE_ctx, void* K_cache, void* V_cache,
                      void* workspace, size_t workspace_bytes, void* hip_stream) {
   (void)workspace; (void)workspace_bytes;
-  return star_attn_phase1_anchor(shape, STAR_ATTN_ANCHOR_FIRST, Q, K, V, nullptr, nullptr, O_ctx,
-                                 LSE_ctx, K_cache, V_cache, nullptr, 0, hip_stream);
+  return phase1_impl(shape, STAR_ATTN_ANCHOR_FIRST, nullptr, const_cast<void*>(Q), K, V, nullptr,
+                     nullptr, O_ctx, LSE_ctx, K_cache, V_cache, nullptr, 0, hip_stream);
 }
 
-int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
-                     const void* Qq, const void* Kq, const void* Vq,
-                     void* K_cache, void* V_cache, float* O_part, float* LSE_part, void* O,
-                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+int star_attn_phase1_rope(const star_attn_shape* shape, double rope_theta, int64_t pos0, void* Q,
+                          const void* K, const void* V, void* O_ctx, float* LSE_ctx,
+                          void* K_cache, void* V_cache, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Rope rope = {rope_theta, pos0};
+  return phase1_impl(shape, STAR_ATTN_ANCHOR_FIRST, &rope, Q, K, V, nullptr, nullptr, O_ctx,
+                     LSE_ctx, K_cache, V_cache, nullptr, 0, hip_stream);
+}
+
+int star_attn_rope(const star_attn_shape* shape, int32_t n_heads, int64_t n_tokens, int64_t pos0,
+                   double rope_theta, const void* X, void* Y, void* hip_stream) {
   int rc = validate_shape(shape);
   if (rc != STAR_ATTN_OK) return rc;
+  if ((rc = validate_rope(shape, rope_theta, pos0)) != STAR_ATTN_OK) return rc;
+  if (n_heads <= 0 || n_tokens <= 0) return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (!X || !Y) return STAR_ATTN_ERR_NULL_POINTER;
+  if (misaligned(X) || misaligned(Y)) return STAR_ATTN_ERR_MISALIGNED;
+  hipError_t e = launch_rope_rotate(shape->dtype, shape->batch, n_tokens, n_heads, shape->head_dim,
+                                    pos0, rope_theta, X, Y, (hipStream_t)hip_stream);
+  return e == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
+}
+
+}  // extern "C"
+
+// Phase 2 behind both public variants.  With `rope`, Qq is rotated in place and
+// Kq on its way into the cache (new token j sits at pos0 + cache_len + j).
+static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t cache_len,
+                       int64_t q_len, void* Qq, const void* Kq, const void* Vq, void* K_cache,
+                       void* V_cache, float* O_part, float* LSE_part, void* O, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  int rc = validate_shape(shape);
+  if (rc != STAR_ATTN_OK) return rc;
+  if (rope && (rc = validate_rope(shape, rope->theta, rope->pos0)) != STAR_ATTN_OK) return rc;
   if (q_len <= 0 || q_len > (1 << 20) || cache_len < shape->ctx_len) return STAR_ATTN_ERR_INVALID_SHAPE;
   if (cache_len + q_len > shape->cache_capacity) return STAR_ATTN_ERR_CACHE_OVERFLOW;
   if (!Qq || !Kq || !Vq || !K_cache || !V_cache || !O || !workspace) return STAR_ATTN_ERR_NULL_POINTER;
@@ -248,15 +312,29 @@ int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_
   // Algorithm 2: the new tokens' K/V join the cache before they attend.  The
   // streaming decode kernel appends them itself (it reads the new rows from
   // Kq/Vq and writes them to the cache); the other paths use the cache writer.
-  const bool fused_append = shape->dtype == STAR_ATTN_BF16 && plan.decode;
-  if (!fused_append &&
-      launch_cache_write(g, shape->dtype, Kq, Vq, K_cache, V_cache, q_len, cache_len, st) != hipSuccess)
+  // Unrotated keys cannot take the fused route (the decode kernel moves rows with
+  // DMAs): they are rotated into the cache first.
+  const bool fused_append = shape->dtype == STAR_ATTN_BF16 && plan.decode && !rope;
+  if (rope) {
+    const int64_t pos = rope->pos0 + cache_len;
+    if (launch_rope_rotate(shape->dtype, g.B, q_len, g.Hq, g.d, pos, rope->theta, Qq, Qq, st) !=
+            hipSuccess ||
+        launch_rope_cache_write(g, shape->dtype, Kq, K_cache, q_len, cache_len, pos, rope->theta,
+                                st) != hipSuccess ||
+        launch_cache_write(g, shape->dtype, nullptr, Vq, K_cache, V_cache, q_len, cache_len, st) !=
+            hipSuccess)
+      return STAR_ATTN_ERR_LAUNCH_FAILED;
+  } else if (!fused_append && launch_cache_write(g, shape->dtype, Kq, Vq, K_cache, V_cache, q_len,
+                                                 cache_len, st) != hipSuccess) {
     return STAR_ATTN_ERR_LAUNCH_FAILED;
+  }
 
   size_t rows = (size_t)g.B * plan.s_total * g.Hq * (size_t)q_len;
   Phase2Args a;
   a.g = g; a.plan = plan; a.cache_len = cache_len; a.q_len = (int32_t)q_len;
-  a.Qq = Qq; a.Kn = Kq; a.Vn = Vq; a.Kc = K_cache; a.Vc = V_cache;
+  a.Qq = Qq; a.Kc = K_cache; a.Vc = V_cache;
+  a.Kn = fused_append ? Kq : nullptr;
+  a.Vn = fused_append ? Vq : nullptr;
   a.O_sub = (float*)workspace;
   a.LSE_sub = (float*)workspace + rows * g.d;
   hipError_t e;
@@ -269,6 +347,26 @@ int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_
   m.g = g; m.plan = plan; m.q_len = (int32_t)q_len; m.out_bf16 = shape->dtype == STAR_ATTN_BF16;
   m.O_sub = a.O_sub; m.LSE_sub = a.LSE_sub; m.O_part = O_part; m.LSE_part = LSE_part; m.O = O;
   return launch_merge(m, st) == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
+}
+
+extern "C" {
+
+int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
+                     const void* Qq, const void* Kq, const void* Vq,
+                     void* K_cache, void* V_cache, float* O_part, float* LSE_part, void* O,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return phase2_impl(shape, nullptr, cache_len, q_len, const_cast<void*>(Qq), Kq, Vq, K_cache,
+                     V_cache, O_part, LSE_part, O, workspace, workspace_bytes, hip_stream);
+}
+
+int star_attn_phase2_rope(const star_attn_shape* shape, double rope_theta, int64_t pos0,
+                          int64_t cache_len, int64_t q_len, void* Qq, const void* Kq,
+                          const void* Vq, void* K_cache, void* V_cache, float* O_part,
+                          float* LSE_part, void* O, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  Rope rope = {rope_theta, pos0};
+  return phase2_impl(shape, &rope, cache_len, q_len, Qq, Kq, Vq, K_cache, V_cache, O_part,
+                     LSE_part, O, workspace, workspace_bytes, hip_stream);
 }
 
 const char* star_attn_status_string(int status) {

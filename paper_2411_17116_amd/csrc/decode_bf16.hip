@@ -233,12 +233,14 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   src.Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   src.Kn = (const char*)a.Kn + ((size_t)beta * a.q_len * g.Hkv + kvh) * ROWB;
   src.Vn = (const char*)a.Vn + ((size_t)beta * a.q_len * g.Hkv + kvh) * ROWB;
-  src.cache_len = cache_len;
+  // without new-token tensors the caches already hold the appended rows
+  const bool fused_append = a.Kn != nullptr;
+  src.cache_len = fused_append ? cache_len : total;
   src.new_stride = g.Hkv * ROWB;
 
   // Algorithm 2, append: the new tokens whose rows fall into this split's steps
   // join the cache (16 lanes move one 256-byte row of K and of V).
-  if (hi > cache_len) {
+  if (fused_append && hi > cache_len) {
     for (int key = cache_len + (lane >> 4); key < hi; key += 4) {
       const int rel = key - base;
       if (rel < 0 || (rel % stride) >= STEP) continue;      // another split's step

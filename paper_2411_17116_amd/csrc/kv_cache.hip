@@ -17,6 +17,7 @@ __global__ __launch_bounds__(256) void cache_write_kernel(
     int64_t n_vec, int64_t n_tokens, int Hkv, int vpr, int64_t cap, int64_t dst_row) {
   const i32x4* src = blockIdx.y == 0 ? K : V;
   i32x4* dst = blockIdx.y == 0 ? Kc : Vc;
+  if (src == nullptr) return;                 // this tensor is written elsewhere
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n_vec; v += stride) {
     int64_t row = v / vpr;            // (beta, t, g) flattened

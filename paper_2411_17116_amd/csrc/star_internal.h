@@ -70,8 +70,8 @@ struct Phase2Args {
   int64_t cache_len;    // tokens cached before this call
   int32_t q_len;
   const void* Qq;       // [B, q_len, Hq, d]
-  const void* Kn;       // new tokens' K, V [B, q_len, Hkv, d]
-  const void* Vn;
+  const void* Kn;       // new tokens' K, V [B, q_len, Hkv, d]; null: the caches already
+  const void* Vn;       // hold them (decode kernel: nothing to append, read the caches)
   void* Kc;             // caches; the new tokens are already appended unless the
   void* Vc;             // kernel appends them itself (decode path)
   float* O_sub;         // [B, s_total, Hq, q_len, d]   per-split local attention
@@ -111,9 +111,15 @@ __host__ __device__ inline void split_range(const SplitPlan& p, int64_t L, int64
 }
 
 // Host-side launchers (each returns the hipError_t of its launch).
+// K and / or V (a null source is skipped) into rows [dst_row, dst_row + n_tokens).
 hipError_t launch_cache_write(const Geom& g, int dtype, const void* K, const void* V,
                               void* Kc, void* Vc, int64_t n_tokens, int64_t dst_row,
                               hipStream_t st);
+hipError_t launch_rope_rotate(int dtype, int B, int64_t n_tokens, int H, int d, int64_t pos0,
+                              double theta, const void* X, void* Y, hipStream_t st);
+hipError_t launch_rope_cache_write(const Geom& g, int dtype, const void* K, void* Kc,
+                                   int64_t n_tokens, int64_t dst_row, int64_t pos0, double theta,
+                                   hipStream_t st);
 hipError_t launch_phase1_f32(const Phase1Args& a, hipStream_t st);
 hipError_t launch_phase2_f32(const Phase2Args& a, hipStream_t st);
 hipError_t launch_phase1_bf16(const Phase1Args& a, hipStream_t st);

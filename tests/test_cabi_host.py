@@ -40,7 +40,8 @@ def test_header_symbols_are_exported(lib):
     names = re.findall(r"\b(star_attn_[a-z0-9_]+)\s*\(", text)
     assert set(names) >= {"star_attn_phase1", "star_attn_phase2", "star_attn_workspace_bytes",
                           "star_attn_status_string", "star_attn_kernel_path",
-                          "star_attn_phase1_anchor", "star_attn_phase1_workspace_bytes"}
+                          "star_attn_phase1_anchor", "star_attn_phase1_workspace_bytes",
+                          "star_attn_phase1_rope", "star_attn_phase2_rope", "star_attn_rope"}
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -179,3 +180,37 @@ def test_phase1_anchor_variant_arguments(lib):
     assert _p1a(lib, shape, EXT, Ka=0x1008, ws_bytes=need) == ERR["MISALIGNED"]
     assert _p1a(lib, shape, EXT, ws=0x1010, ws_bytes=need) == ERR["MISALIGNED"]
     assert _p1a(lib, shape, EXT, ws_bytes=need - 1) == ERR["WORKSPACE_TOO_SMALL"]
+
+
+def test_rope_entry_point_arguments(lib):
+    shape = good_shape()
+    L = shape.ctx_len
+    d = ctypes.c_double
+
+    def p1r(theta=10000.0, pos0=0, Q=0x1000, K=0x1000):
+        return lib.star_attn_phase1_rope(ctypes.byref(shape), d(theta), pos0, Q, K, 0x1000, 0x1000,
+                                         None, 0x1000, 0x1000, None, 0, None)
+
+    def p2r(theta=10000.0, pos0=0, Qq=0x1000, ws_bytes=64):
+        return lib.star_attn_phase2_rope(ctypes.byref(shape), d(theta), pos0, L, 1, Qq, 0x1000,
+                                         0x1000, 0x1000, 0x1000, None, None, 0x1000, 0x1000,
+                                         ws_bytes, None)
+
+    def rot(theta=10000.0, pos0=0, heads=8, tokens=4, X=0x1000, Y=0x1000):
+        return lib.star_attn_rope(ctypes.byref(shape), heads, tokens, pos0, d(theta), X, Y, None)
+
+    for bad_theta in (0.0, 1.0, -5.0, float("inf"), float("nan")):
+        assert p1r(theta=bad_theta) == ERR["INVALID_SHAPE"]
+        assert p2r(theta=bad_theta) == ERR["INVALID_SHAPE"]
+        assert rot(theta=bad_theta) == ERR["INVALID_SHAPE"]
+    assert p1r(pos0=-1) == ERR["INVALID_SHAPE"]
+    assert p2r(pos0=-1) == ERR["INVALID_SHAPE"]
+    assert rot(pos0=-1) == ERR["INVALID_SHAPE"]
+    assert p1r(Q=None) == ERR["NULL_POINTER"]
+    assert p1r(K=0x1004) == ERR["MISALIGNED"]
+    assert p2r(Qq=None) == ERR["NULL_POINTER"]
+    assert p2r() == ERR["WORKSPACE_TOO_SMALL"]
+    assert rot(heads=0) == ERR["INVALID_SHAPE"]
+    assert rot(tokens=0) == ERR["INVALID_SHAPE"]
+    assert rot(X=None) == ERR["NULL_POINTER"]
+    assert rot(Y=0x1002) == ERR["MISALIGNED"]
