@@ -286,6 +286,32 @@ def decode_graph(cfg, shape, bufs, reps=5):
             "note": f"{cfg.nd} decode calls captured into one HIP graph, median of {reps} replays"}
 
 
+def rope_cost(cfg, shape, inp, bufs, theta=500000.0):
+    """What unrotated inputs cost: the in-place rotation of Q alone (an HBM
+    stream: Q read once and written once) and the whole phase-1 call with the
+    rotation inside (Q in place, K on its way into the cache)."""
+    Qs = inp.Q.clone()                 # rotated over and over; norms are preserved
+    t = Timer()
+    idx = []
+    for _ in range(3):
+        e = t.start()
+        sa.rope(shape, Qs, Qs, theta)
+        idx.append(t.stop(e))
+    idp = []
+    for _ in range(3):
+        e = t.start()
+        sa.phase1_rope(shape, theta, Qs, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+        idp.append(t.stop(e))
+    torch.cuda.synchronize()
+    q_ms = min(t.ms(i) for i in idx[1:])
+    p_ms = min(t.ms(i) for i in idp[1:])
+    q_bytes = 2.0 * Qs.numel() * Qs.element_size()
+    return {"q_rotate_ms": q_ms, "q_rotate_gb_per_s": q_bytes / (q_ms * 1e-3) / 1e9,
+            "q_rotate_hbm_frac": q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "phase1_rope_ms": p_ms, "theta": theta,
+            "note": "star_attn_rope on Q in place (bytes = Q read + written), and star_attn_phase1_rope"}
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summaries
     (profiles/traffic.json), or None if that kernel/workload was not profiled."""
@@ -307,6 +333,8 @@ def main():
     ap.add_argument("--no-full-causal", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph replay of the decode loop")
+    ap.add_argument("--no-rope", action="store_true",
+                    help="skip timing the entry points that take unrotated projections")
     ap.add_argument("--no-power", action="store_true",
                     help="skip the sustained phase-1 run with power / clock polling")
     ap.add_argument("--calib-copy", action="store_true",
@@ -423,6 +451,9 @@ def main():
                               "flop_ratio_vs_star": f_flops / flops}
     if "decode" in sections and cfg.nd and not args.no_graph:
         out["phase2"]["decode_graph"] = decode_graph(cfg, shape, bufs)
+    if "phase1" in sections and not args.no_rope:
+        out["rope"] = rope_cost(cfg, shape, inp, bufs)
+        # the caches now hold rotated keys; nothing below reads them
     if poller is not None:
         if "phase1" in sections:
             out["power"] = sustained_phase1(cfg, shape, inp, bufs, poller)
