@@ -38,15 +38,9 @@ static Geom make_geom(const star_attn_shape* s) {
 static int64_t ceil_div(int64_t x, int64_t y) { return (x + y - 1) / y; }
 static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
 
-// Heads of one KV group that share a workgroup in the bf16 row-tiled kernels:
-// the largest of 8, 4, 2, 1 that divides G and fits the workgroup's 32-row blocks.
-int heads_per_workgroup(int G, int row_blocks) {
-  for (int h = 8; h > 1; h >>= 1)
-    if (h <= row_blocks && G % h == 0) return h;
-  return 1;
-}
-
-int flash_row_blocks();   // 32-row blocks per workgroup of the phase-2 row-tiled kernel
+// Row tiling of the bf16 row-tiled kernels (defined with them).
+int flash_heads_per_workgroup(int G);
+int flash_tokens_per_workgroup(int G);
 
 // Workgroups of the decode kernel that are resident at once on an MI355X:
 // 256 CUs x 2 (the kernel's 64 KiB LDS ring allows two per CU).
@@ -95,8 +89,8 @@ static bool make_plan(const star_attn_shape* s, int64_t q_len, int64_t total, bo
     if (s->dtype == STAR_ATTN_F32) {
       wgs = (int64_t)g.B * g.Hq * ceil_div(q_len, 64);
     } else {
-      int hpw = heads_per_workgroup(g.G, flash_row_blocks());
-      wgs = (int64_t)g.B * g.Hkv * (g.G / hpw) * ceil_div(q_len, 32 * flash_row_blocks() / hpw);
+      wgs = (int64_t)g.B * g.Hkv * (g.G / flash_heads_per_workgroup(g.G)) *
+            ceil_div(q_len, flash_tokens_per_workgroup(g.G));
     }
     // one thread walks a whole split in the fp32 kernel, so short calls are cut
     // much finer there (down to one 32-key LDS tile per split)

@@ -5,7 +5,7 @@
 //
 // Shape of the computation
 //   * A workgroup is 8 wavefronts (two per SIMD, one workgroup per CU); each
-//     wavefront owns 32 query rows and the whole head dimension.  The rows of a
+//     wavefront owns 32 query rows (two blocks of 16) and the whole head dimension.  The rows of a
 //     workgroup are GQA-packed: up to 8 query heads of one KV group times 32 to
 //     256 tokens, so the K/V tiles a workgroup streams are fetched from L2 once
 //     per 256 rows, and the wavefronts' causal frontiers lie within those tokens.
@@ -15,13 +15,17 @@
 //     XOR-swizzled so that both the K operand reads (ds_read_b128) and the
 //     transposing V operand reads (ds_read_b64_tr_b16) are bank-conflict free
 //     without padding.
-//   * S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q^T
-//     held in registers for the whole kernel).  Computing the transposed score
-//     tile leaves each lane with 16 keys of ONE query row, so the row maximum
-//     and sum are in-lane reductions plus a single cross-half exchange, and the
-//     exponentiated tile is already laid out as the B operand of the second
-//     MFMA: O^T += V^T P^T, with V^T fragments produced by the LDS transposing
-//     read.  P never touches LDS.
+//   * S^T = K Q^T with v_mfma_f32_16x16x32_bf16 (A = K rows from LDS, B = Q^T
+//     held in registers for the whole kernel); a wavefront's 32 rows are two
+//     column blocks of 16, and every K / V^T fragment read from LDS feeds both.
+//     (The 16x16x32 shape moves a quarter of the accumulator registers per
+//     instruction of the 32x32x16 one; at this chip's power limit it sustains
+//     about 10 % more flops.)  Computing the transposed score tile leaves each
+//     lane with keys of ONE query row, so row sums are in-lane and a row
+//     maximum is an exchange among four lanes, and the exponentiated tile is
+//     already laid out as the B operand of the second MFMA: O^T += V^T P^T,
+//     with V^T fragments produced by the LDS transposing read.  P never
+//     touches LDS.
 //   * Softmax runs in the log2 domain in fp32 against a reference maximum taken
 //     from the row's first 32 keys: the common path is one fma + one exp per
 //     score, a packed bf16 conversion and a dot2 for the row sum, with no
@@ -37,13 +41,14 @@
 
 namespace star {
 
-int heads_per_workgroup(int G, int row_blocks);   // defined with the split plan
+int flash_heads_per_workgroup(int G);
+int flash_tokens_per_workgroup(int G);
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
@@ -60,6 +65,8 @@ constexpr int LDS_K0 = 0, LDS_K1 = TILEB, LDS_V0 = 2 * TILEB, LDS_V1 = 3 * TILEB
 #endif
 constexpr int NW = STAR_FLASH_WAVES;
 constexpr int NT = 64 * NW;                // threads per workgroup
+constexpr int RB = 2;                      // 16-row blocks per wavefront
+constexpr int WG_BLOCKS = NW * RB;         // 16-row blocks per workgroup
 constexpr int DMA_ROWS = NT / 16;          // key rows one DMA instruction of the workgroup moves
 constexpr int DMA_ITERS = TKEYS / DMA_ROWS;
 static_assert(NW == 4 || NW == 8, "tile DMA is written for 4 or 8 wavefronts");
@@ -69,7 +76,9 @@ constexpr float LN2 = 0.6931471805599453f;
 #define LDS_AS __attribute__((address_space(3)))
 
 // chunk swizzle of a key row: chunk c of row r is stored in slot c ^ swz(r)
-__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+// (a rotation of the row's low four bits: conflict-free for the 16-row K operand
+// read and for the 4-row transposing V read)
+__device__ __forceinline__ int swz(int r) { return ((r << 1) & 15) | ((r >> 3) & 1); }
 
 // 16-byte DMA global -> LDS: lane L's data lands at lds_base + 16 * L.  The
 // global address is sbase + voff (unsigned 32-bit byte offset per lane).
@@ -88,12 +97,17 @@ __device__ __forceinline__ bf16x4 lds_read_tr16(unsigned addr) {
   return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(addr)));
 }
 
-__device__ __forceinline__ float pair_max(float x) {
-  // both lanes of a (l, l^32) pair receive max(x[l], x[l^32])
+// The four lanes l, l^16, l^32, l^48 hold the keys of one query row.
+__device__ __forceinline__ float xor16(float x) {
+  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401F));
+}
+__device__ __forceinline__ float quad_max(float x) {
+  x = fmaxf(x, xor16(x));
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-__device__ __forceinline__ float pair_sum(float x) {
+__device__ __forceinline__ float quad_sum(float x) {
+  x += xor16(x);
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
@@ -129,14 +143,12 @@ struct TileSeq {
   __device__ __forceinline__ const char* vbase(int idx) const { return idx < n_a ? Va : Vl; }
 };
 
-// RB = row blocks of 32 query rows per wavefront.  Every K / V^T fragment read
-// from LDS feeds RB MFMAs, so RB = 2 halves the LDS traffic per flop (with RB = 1
-// the 4 SIMDs of a CU ask LDS for ~1 KiB per MFMA, which is its whole bandwidth).
-template <int RB>
+// A wavefront's state.  Lane (col = lane % 16, j4 = lane / 16) belongs to query
+// row `col` of each of the wavefront's RB 16-row blocks.
 struct WaveState {
-  bf16x8 q[RB][8];    // Q^T fragments: q[rb][t] = Q[row lane%32 of block rb][16t + 8*(lane/32) .. +7]
-  f32x16 o[RB][4];    // O^T accumulators: o[rb][dt][v] = O[row][32dt + 8(v/4) + 4(lane/32) + v%4]
-  float m[RB];        // reference maximum of the raw logits (pair-uniform)
+  bf16x8 q[RB][4];    // Q^T fragments: q[rb][t] = Q[row col of block rb][32t + 8 j4 .. +7]
+  f32x4 o[RB][8];     // O^T accumulators: o[rb][dt][v] = O[row][16 dt + 4 j4 + v]
+  float m[RB];        // reference maximum of the raw logits (uniform over a row's four lanes)
   float neg_mc[RB];   // -m * c (0 while m == -inf)
   float l[RB];        // this lane's share of the running sum of 2^((s-m) c)
   float lmax;         // largest per-unit partial row sum seen by the fast loop
@@ -144,11 +156,11 @@ struct WaveState {
 
 // Per-lane LDS addresses and DMA offsets, fixed for the whole kernel.
 struct LaneAddr {
-  unsigned k[8];       // K operand: row lane%32, chunk 2t + lane/32 (swizzled)
-  unsigned v[4][2];    // V^T operand: see attend()
+  unsigned k[4];       // K operand: row col, chunk 4t + j4 (swizzled)
+  unsigned v[8];       // V^T operand: see lane_addr()
   unsigned dma;        // byte offset of this thread's 16-byte unit in row tid/16
   int tid;
-  int half;
+  int j4;
 };
 
 // Issue the DMA of one 64-key tile of K or V into an LDS tile buffer.  Thread
@@ -174,7 +186,10 @@ __device__ __forceinline__ void issue_tile(const char* base, int key0, int hi, u
   }
 }
 
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+// A 32-key score unit of one row block: s[kt][v] is key 16 kt + 4 j4 + v.
+struct Scores {
+  f32x4 s[2];
+};
 
 // The fast key loop keeps ONE reference maximum per row, taken from the row's
 // first 32 keys, and never rescales: p = 2^(s c - m c) against any fixed m gives
@@ -184,40 +199,38 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 // softmax (SAFE mode), which searches the maximum of every unit.
 constexpr float LSUM_LIMIT = 1.152921504606846976e18f;   // 2^60
 
-__device__ __forceinline__ float unit_max(const f32x16& s) {
-  float t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
-  float t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
-  float t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
-  float t3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
-  float t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
-  return pair_max(fmaxf(fmaxf(fmaxf(t0, t1), fmaxf(t2, t3)), fmaxf(t4, s[15])));
+__device__ __forceinline__ float unit_max(const Scores& x) {
+  float t0 = fmaxf(fmaxf(x.s[0][0], x.s[0][1]), fmaxf(x.s[0][2], x.s[0][3]));
+  float t1 = fmaxf(fmaxf(x.s[1][0], x.s[1][1]), fmaxf(x.s[1][2], x.s[1][3]));
+  return quad_max(fmaxf(t0, t1));
 }
 
-// Softmax numerators of one 32-key score tile against a reference maximum:
+// Softmax numerators of one 32-key score unit against a reference maximum:
 // p = 2^(s c - m c) rounded to bf16, and the lane's sum of the ROUNDED values
 // (v_dot2 with a vector of ones), so numerator and denominator see the same
-// rounding.
-__device__ __forceinline__ float softmax_unit(const f32x16& s, float neg_mc, bf16x8 (&p)[2], float c) {
+// rounding.  Slot 4 kt + v of p is key 16 kt + 4 j4 + v.
+__device__ __forceinline__ float softmax_unit(const Scores& x, float neg_mc, bf16x8& p, float c) {
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   float lsum = 0.f;
 #pragma unroll
-  for (int v = 0; v < 16; v += 2) {
-    bf16x2 pr;
-    pr[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v], c, neg_mc));
-    pr[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[v + 1], c, neg_mc));
-    p[v / 8][v % 8] = pr[0];
-    p[v / 8][v % 8 + 1] = pr[1];
-    lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
-  }
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; v += 2) {
+      bf16x2 pr;
+      pr[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(x.s[kt][v], c, neg_mc));
+      pr[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(x.s[kt][v + 1], c, neg_mc));
+      p[4 * kt + v] = pr[0];
+      p[4 * kt + v + 1] = pr[1];
+      lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
+    }
   return lsum;
 }
 
 // Raise the reference of row block rb to the maximum seen so far; returns the
 // factor alpha = 2^((m_old - m_new) c) for everything accumulated before (0 while
 // nothing was visible yet, 1 if the maximum did not move).
-template <int RB>
-__device__ __forceinline__ float raise_reference(WaveState<RB>& w, int rb, const f32x16& s, float c) {
-  float m_new = fmaxf(w.m[rb], unit_max(s));
+__device__ __forceinline__ float raise_reference(WaveState& w, int rb, const Scores& x, float c) {
+  float m_new = fmaxf(w.m[rb], unit_max(x));
   float mm = m_new == -INFINITY ? 0.f : m_new;
   float alpha = __builtin_amdgcn_exp2f((w.m[rb] - mm) * c);
   w.m[rb] = m_new;
@@ -225,8 +238,7 @@ __device__ __forceinline__ float raise_reference(WaveState<RB>& w, int rb, const
   return alpha;
 }
 
-template <int RB>
-__device__ __forceinline__ void rescale(WaveState<RB>& w, const float (&alpha)[RB]) {
+__device__ __forceinline__ void rescale(WaveState& w, const float (&alpha)[RB]) {
   bool moved = false;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) moved |= alpha[rb] != 1.0f;
@@ -234,29 +246,49 @@ __device__ __forceinline__ void rescale(WaveState<RB>& w, const float (&alpha)[R
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) w.o[rb][dt][v] *= alpha[rb];
+      for (int dt = 0; dt < 8; ++dt) w.o[rb][dt] *= alpha[rb];
   }
 }
 
-// Causal / range-end mask of one 32-key score tile: element v is key
-// key0 + 8(v/4) + 4*half + v%4 and is visible iff it is below `lim`.
-__device__ __forceinline__ void mask_unit(f32x16& s, int key0, int lim, int half) {
-  int x = lim - key0 - 4 * half;
+// Causal / range-end mask of one 32-key score unit: element (kt, v) is key
+// key0 + 16 kt + 4 j4 + v and is visible iff it is below `lim`.
+__device__ __forceinline__ void mask_unit(Scores& x, int key0, int lim, int j4) {
+  int y = lim - key0 - 4 * j4;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) s[v] = (8 * (v / 4) + (v % 4)) < x ? s[v] : -INFINITY;
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) x.s[kt][v] = (16 * kt + v) < y ? x.s[kt][v] : -INFINITY;
 }
 
-// Mask the score tiles of a unit [key0, key0 + 32) where some row of the
-// wavefront cannot see all of it (wave_lo = smallest causal bound in the wave).
-template <int RB>
-__device__ __forceinline__ void mask_if_needed(f32x16 (&s)[RB], int key0, int hi, int wave_lo,
-                                               const int (&row_lim)[RB], int half) {
+// Mask the score units [key0, key0 + 32) where some row of the wavefront cannot
+// see all of it (wave_lo = smallest causal bound in the wave).
+__device__ __forceinline__ void mask_if_needed(Scores (&s)[RB], int key0, int hi, int wave_lo,
+                                               const int (&row_lim)[RB], int j4) {
   if (key0 + 32 > wave_lo || key0 + 32 > hi) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) mask_unit(s[rb], key0, row_lim[rb] < hi ? row_lim[rb] : hi, half);
+    for (int rb = 0; rb < RB; ++rb) mask_unit(s[rb], key0, row_lim[rb] < hi ? row_lim[rb] : hi, j4);
   }
+}
+
+// PRE_IN: the first two K and V^T fragments were already read by the previous
+// stage and arrive in `pre`; PRE_OUT: this stage reads the first two fragment
+// pairs of the next stage (LDS offsets NKOFF / NVOFF) into `pre` behind its last
+// MFMAs, so that the next stage starts without waiting for LDS.
+struct PreFrag {
+  bf16x8 k[2], v[2];
+};
+
+// K fragment i = 4 kt + t of a 32-key unit: keys 16 kt .. +15, d 32 t .. +31.
+__device__ __forceinline__ bf16x8 read_k(const LaneAddr& la, int i, int off) {
+  return lds_read_b128(la.k[i & 3] + off + (i >> 2) * 16 * ROWB);
+}
+// V^T fragment dt of a 32-key unit: d 16 dt .. +15; slot e of lane group j4 is key
+// 4 j4 + e (e < 4) or 16 + 4 j4 + e - 4, matching the slots of p: two transposing
+// reads, 16 key rows apart.
+__device__ __forceinline__ bf16x8 read_v(const LaneAddr& la, int dt, int off) {
+  bf16x4 lo = lds_read_tr16(la.v[dt] + off);
+  bf16x4 hi = lds_read_tr16(la.v[dt] + off + 16 * ROWB);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // One pipeline stage holds three independent pieces of work:
@@ -270,26 +302,18 @@ __device__ __forceinline__ void mask_if_needed(f32x16 (&s)[RB], int key0, int hi
 // receives the rescale factors for the accumulators (SAFE mode; 1 otherwise), to
 // be applied after the stage, i.e. after the PV MFMAs of unit u-1 and before
 // those of unit u.
-// PRE_IN: the first two K and V^T fragments were already read by the previous
-// stage and arrive in `pre`; PRE_OUT: this stage reads the first two fragment
-// pairs of the next stage (LDS offsets NKOFF / NVOFF) into `pre` behind its last
-// MFMAs, so that the next stage starts without waiting for LDS.
-struct PreFrag {
-  bf16x8 k[2], v[2];
-};
-
-template <int RB, bool SAFE, bool QK, bool SM, bool PV, int KOFF, int VOFF, bool PRE_IN = false,
+template <bool SAFE, bool QK, bool SM, bool PV, int KOFF, int VOFF, bool PRE_IN = false,
           bool PRE_OUT = false, int NKOFF = 0, int NVOFF = 0>
-__device__ __forceinline__ void stage(WaveState<RB>& w, const LaneAddr& la, f32x16 (&s_next)[RB],
-                                      f32x16 (&s_cur)[RB], bf16x8 (&p_cur)[RB][2],
-                                      const bf16x8 (&p_prev)[RB][2], float c, float (&alpha)[RB],
+__device__ __forceinline__ void stage(WaveState& w, const LaneAddr& la, Scores (&s_next)[RB],
+                                      Scores (&s_cur)[RB], bf16x8 (&p_cur)[RB],
+                                      const bf16x8 (&p_prev)[RB], float c, float (&alpha)[RB],
                                       PreFrag& pre) {
   bf16x8 kf[8], vf[8];
   // Keep this stage's softmax inside the stage: without the anchors the optimizer
   // hoists it above the preceding barrier and sinks the row sums to the loop end.
   if (SM) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(s_cur[rb]));
+    for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(s_cur[rb].s[0]), "+v"(s_cur[rb].s[1]));
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -298,24 +322,14 @@ __device__ __forceinline__ void stage(WaveState<RB>& w, const LaneAddr& la, f32x
       vf[i] = pre.v[i];
       continue;
     }
-    if (QK) kf[i] = lds_read_b128(la.k[i] + KOFF);
-    if (PV) {
-      // B operand p_prev[.][hf]: slot e of lane half h is key 16hf + 8(e/4) + 4h + e%4,
-      // so the A operand needs, for d-row lane%32, keys k0..k0+3 and k0+8..k0+11
-      // with k0 = 16hf + 4h: two transposing reads.
-      const int hf = i >> 2, dt = i & 3;
-      bf16x4 lo = lds_read_tr16(la.v[dt][0] + VOFF + 16 * hf * ROWB);
-      bf16x4 hi = lds_read_tr16(la.v[dt][1] + VOFF + 16 * hf * ROWB);
-      vf[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    }
+    if (QK) kf[i] = read_k(la, i, KOFF);
+    if (PV) vf[i] = read_v(la, i, VOFF);
   }
   if (PRE_OUT) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      pre.k[i] = lds_read_b128(la.k[i] + NKOFF);
-      bf16x4 lo = lds_read_tr16(la.v[i][0] + NVOFF);
-      bf16x4 hi = lds_read_tr16(la.v[i][1] + NVOFF);
-      pre.v[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      pre.k[i] = read_k(la, i, NKOFF);
+      pre.v[i] = read_v(la, i, NVOFF);
     }
   }
 #pragma unroll
@@ -331,43 +345,42 @@ __device__ __forceinline__ void stage(WaveState<RB>& w, const LaneAddr& la, f32x
         w.lmax = fmaxf(w.lmax, lsum);
       }
     }
-    if (QK) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s_next[rb][v] = 0.f;
-    }
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     if (QK) {
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        s_next[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], w.q[rb][i], s_next[rb], 0, 0, 0);
+      for (int rb = 0; rb < RB; ++rb) {
+        // the first d-chunk of a 16-key sub-unit starts from zero (an inline constant)
+        const f32x4 acc = (i & 3) == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : s_next[rb].s[i >> 2];
+        s_next[rb].s[i >> 2] =
+            __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i], w.q[rb][i & 3], acc, 0, 0, 0);
+      }
     }
     if (PV) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
-        w.o[rb][i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[rb][i >> 2],
-                                                                 w.o[rb][i & 3], 0, 0, 0);
+        w.o[rb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[i], p_prev[rb], w.o[rb][i], 0, 0, 0);
     }
   }
   if (QK && SM && PV) {
     if (!PRE_IN) __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-#pragma unroll
-      for (int k = 0; k < RB; ++k) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 3, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (k == RB - 1 && (i < 6 || PRE_OUT)) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 5 : 4, 0);
-      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < 6 || PRE_OUT) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 2, 0);
     }
   }
   if (SM) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-      asm volatile("" : "+v"(w.l[rb]), "+v"(p_cur[rb][0]), "+v"(p_cur[rb][1]));
+    for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(w.l[rb]), "+v"(p_cur[rb]));
     asm volatile("" : "+v"(w.lmax));
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -380,16 +393,15 @@ __device__ __forceinline__ void stage(WaveState<RB>& w, const LaneAddr& la, f32x
 //   stage B: scores of unit 2t+3 | softmax of unit 2t+2 | PV of unit 2t+1.
 // MORE = tile t+1 exists.  KN / VC are the LDS offsets of K tile t+1 and V tile t,
 // KF / VF those of the buffers that are refilled (K tile t+2, V tile t+1).
-template <int RB>
 struct LoopRegs {
-  f32x16 sA[RB], sB[RB];          // score tiles of the even / odd 32-key unit
-  bf16x8 pA[RB][2], pB[RB][2];    // their exponentials (bf16)
+  Scores sA[RB], sB[RB];      // score units of the even / odd 32-key unit
+  bf16x8 pA[RB], pB[RB];      // their exponentials (bf16)
 };
 
-template <int RB, bool SAFE, bool MORE, int KN, int VC, int KF, int VF>
-__device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, const TileSeq& seq,
+template <bool SAFE, bool MORE, int KN, int VC, int KF, int VF>
+__device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, const TileSeq& seq,
                                           int t, const int (&row_lim)[RB], int wave_lo, float c,
-                                          unsigned lds0, LoopRegs<RB>& r) {
+                                          unsigned lds0, LoopRegs& r) {
   constexpr int H = 32 * ROWB;
   float alpha[RB];
   PreFrag pre;
@@ -404,18 +416,17 @@ __device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, 
     int nk0, nhi;
     seq.tile(t + 1, &nk0, &nhi);
     issue_tile(seq.vbase(t + 1), nk0, nhi, lds0 + VF, la);
-    stage<RB, SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB,
-                                                                           r.pA, c, alpha, pre);
+    stage<SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB, r.pA,
+                                                                       c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    mask_if_needed<RB>(r.sA, nk0, nhi, wave_lo, row_lim, la.half);
-    stage<RB, SAFE, true, true, true, KN + H, VC + H, true>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha,
-                                                            pre);
+    mask_if_needed(r.sA, nk0, nhi, wave_lo, row_lim, la.j4);
+    stage<SAFE, true, true, true, KN + H, VC + H, true>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    mask_if_needed<RB>(r.sB, nk0 + 32, nhi, wave_lo, row_lim, la.half);
+    mask_if_needed(r.sB, nk0 + 32, nhi, wave_lo, row_lim, la.j4);
   } else {
-    stage<RB, SAFE, false, true, true, 0, VC>(w, la, r.sA, r.sB, r.pB, r.pA, c, alpha, pre);
+    stage<SAFE, false, true, true, 0, VC>(w, la, r.sA, r.sB, r.pB, r.pA, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    stage<RB, SAFE, false, false, true, 0, VC + H>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha, pre);
+    stage<SAFE, false, false, true, 0, VC + H>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha, pre);
   }
 }
 
@@ -424,13 +435,13 @@ __device__ __forceinline__ void tile_step(WaveState<RB>& w, const LaneAddr& la, 
 //   row_lim     this lane's exclusive causal key bound per row block (0 = inactive row)
 //   wave_lo     smallest row_lim among the wavefront's active rows: key tiles that
 //               end at or below it need no causal mask
-template <int RB, bool SAFE>
-__device__ __forceinline__ void key_loop(WaveState<RB>& w, const LaneAddr& la, const TileSeq& seq,
+template <bool SAFE>
+__device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const TileSeq& seq,
                                          const int (&row_lim)[RB], int wave_lo, float c,
                                          unsigned lds0) {
   const int T = seq.n_tiles;
   constexpr int K0 = LDS_K0, K1 = LDS_K1, V0 = LDS_V0, V1 = LDS_V1, H = 32 * ROWB;
-  LoopRegs<RB> r;
+  LoopRegs r;
   float alpha[RB];
   PreFrag pre;
   int key0, hi;
@@ -448,10 +459,10 @@ __device__ __forceinline__ void key_loop(WaveState<RB>& w, const LaneAddr& la, c
     wait_vmcnt0();
   }
   __builtin_amdgcn_s_barrier();
-  stage<RB, SAFE, true, false, false, K0, 0>(w, la, r.sA, r.sA, r.pA, r.pA, c, alpha, pre);
-  mask_if_needed<RB>(r.sA, key0, hi, wave_lo, row_lim, la.half);
-  stage<RB, SAFE, true, false, false, K0 + H, 0>(w, la, r.sB, r.sA, r.pA, r.pA, c, alpha, pre);
-  mask_if_needed<RB>(r.sB, key0 + 32, hi, wave_lo, row_lim, la.half);
+  stage<SAFE, true, false, false, K0, 0>(w, la, r.sA, r.sA, r.pA, r.pA, c, alpha, pre);
+  mask_if_needed(r.sA, key0, hi, wave_lo, row_lim, la.j4);
+  stage<SAFE, true, false, false, K0 + H, 0>(w, la, r.sB, r.sA, r.pA, r.pA, c, alpha, pre);
+  mask_if_needed(r.sB, key0 + 32, hi, wave_lo, row_lim, la.j4);
   // first unit: its row maximum becomes the reference (nothing to rescale yet)
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
@@ -464,25 +475,22 @@ __device__ __forceinline__ void key_loop(WaveState<RB>& w, const LaneAddr& la, c
   // and the accumulators flow through straight-line code.
   int t = 0;
   for (; t + 2 < T; t += 2) {
-    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
-    tile_step<RB, SAFE, true, K0, V1, K1, V0>(w, la, seq, t + 1, row_lim, wave_lo, c, lds0, r);
+    tile_step<SAFE, true, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<SAFE, true, K0, V1, K1, V0>(w, la, seq, t + 1, row_lim, wave_lo, c, lds0, r);
   }
   if (T - t == 2) {
-    tile_step<RB, SAFE, true, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
-    tile_step<RB, SAFE, false, K0, V1, K1, V0>(w, la, seq, t + 1, row_lim, wave_lo, c, lds0, r);
+    tile_step<SAFE, true, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<SAFE, false, K0, V1, K1, V0>(w, la, seq, t + 1, row_lim, wave_lo, c, lds0, r);
   } else {
-    tile_step<RB, SAFE, false, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
+    tile_step<SAFE, false, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
   }
 }
 
-template <int RB>
-__device__ __forceinline__ void reset_state(WaveState<RB>& w) {
+__device__ __forceinline__ void reset_state(WaveState& w) {
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) w.o[rb][dt][v] = 0.f;
+    for (int dt = 0; dt < 8; ++dt) w.o[rb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     w.m[rb] = -INFINITY;
     w.neg_mc[rb] = 0.f;
     w.l[rb] = 0.f;
@@ -490,43 +498,40 @@ __device__ __forceinline__ void reset_state(WaveState<RB>& w) {
   w.lmax = 0.f;
 }
 
-// Attention of the workgroup's rows over a tile sequence: the fast loop, and the
-// exact loop again if any wavefront's scores left the fast loop's safe range.
-template <int RB>
-__device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq,
-                                       const int (&row_lim)[RB], int wave_lo, float c,
-                                       unsigned lds0) {
+// LDS addresses of the calling lane.
+__device__ __forceinline__ LaneAddr lane_addr(unsigned lds0) {
   LaneAddr la;
   la.tid = threadIdx.x;
   const int lane = la.tid & 63;
-  la.half = lane >> 5;
-  const int i32 = lane & 31;
-  {
-    int x = la.half ^ swz(i32);
+  const int col = lane & 15;
+  la.j4 = lane >> 4;
+  // K operand: lane (col, j4) reads row col, chunk 4t + j4
 #pragma unroll
-    for (int t = 0; t < 8; ++t) la.k[t] = lds0 + i32 * ROWB + (((2 * t) ^ x) << 4);
-    // V^T operand: source lane addresses row 4*half + (lane%16)/4 (+8 for the
-    // second read), columns 32dt + 16*((lane/16)%2) + 4*(lane%4) .. +3
-    int q4 = (lane & 15) >> 2, gi = (lane >> 4) & 1;
+  for (int t = 0; t < 4; ++t) la.k[t] = lds0 + col * ROWB + (((4 * t + la.j4) ^ swz(col)) << 4);
+  // V^T operand: source lane addresses row 4 j4 + col/4 (+16 for the second
+  // read), columns 16 dt + 4 (lane % 4) .. +3
+  const int rr = 4 * la.j4 + (col >> 2);
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        int r = 4 * la.half + q4 + 8 * u;
-        int chunk = 4 * dt + 2 * gi + ((lane & 3) >> 1);
-        la.v[dt][u] = lds0 + r * ROWB + ((chunk ^ swz(r)) << 4) + 8 * (lane & 1);
-      }
-    unsigned chunk_off = ((la.tid & 15) ^ swz(la.tid >> 4)) << 4;
-    la.dma = (la.tid >> 4) * ROWB + chunk_off;
-  }
+  for (int dt = 0; dt < 8; ++dt)
+    la.v[dt] = lds0 + rr * ROWB + (((2 * dt + ((lane & 3) >> 1)) ^ swz(rr)) << 4) + 8 * (lane & 1);
+  unsigned chunk_off = ((la.tid & 15) ^ swz(la.tid >> 4)) << 4;
+  la.dma = (la.tid >> 4) * ROWB + chunk_off;
+  return la;
+}
+
+// Attention of the workgroup's rows over a tile sequence: the fast loop, and the
+// exact loop again if any wavefront's scores left the fast loop's safe range.
+__device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const int (&row_lim)[RB],
+                                       int wave_lo, float c, unsigned lds0) {
+  const LaneAddr la = lane_addr(lds0);
   if (seq.n_tiles == 0) return;
   // Consume the Q fragments here so that the compiler places its own wait for
   // their loads before the first DMA is in flight (and none inside the loops).
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(w.q[rb][t]));
-  key_loop<RB, false>(w, la, seq, row_lim, wave_lo, c, lds0);
+    for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(w.q[rb][t]));
+  key_loop<false>(w, la, seq, row_lim, wave_lo, c, lds0);
 
   // Did any row of any wavefront leave the safe range?  One LDS word per
   // wavefront; __syncthreads() (fence + barrier) orders the tile reads before the
@@ -534,7 +539,7 @@ __device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq,
   __syncthreads();
   const bool bad = __builtin_amdgcn_ballot_w64(!(w.lmax < LSUM_LIMIT)) != 0;
   LDS_AS int* flags = (LDS_AS int*)(size_t)lds0;
-  if (lane == 0) flags[la.tid >> 6] = bad ? 1 : 0;
+  if ((la.tid & 63) == 0) flags[la.tid >> 6] = bad ? 1 : 0;
   __syncthreads();
   int any_bad = 0;
 #pragma unroll
@@ -542,31 +547,29 @@ __device__ __forceinline__ void attend(WaveState<RB>& w, const TileSeq& seq,
   __syncthreads();
   if (__builtin_expect(any_bad != 0, 0)) {
     reset_state(w);
-    key_loop<RB, true>(w, la, seq, row_lim, wave_lo, c, lds0);
+    key_loop<true>(w, la, seq, row_lim, wave_lo, c, lds0);
   }
 }
 
-template <int RB>
-__device__ __forceinline__ void load_q(WaveState<RB>& w, int rb, const char* qrow, int half) {
+__device__ __forceinline__ void load_q(WaveState& w, int rb, const char* qrow, int j4) {
 #pragma unroll
-  for (int t = 0; t < 8; ++t) w.q[rb][t] = *(const bf16x8*)(qrow + (16 * t + 8 * half) * 2);
+  for (int t = 0; t < 4; ++t) w.q[rb][t] = *(const bf16x8*)(qrow + (32 * t + 8 * j4) * 2);
 }
 
-// Row block g of a workgroup (g = wave * RB + rb, NW * RB of them) is head g % hpw of
-// the workgroup's head group and token block g / hpw: the heads of a KV group
-// come first, so that a wavefront's row blocks share their tokens (and their
-// causal frontier) whenever the group has at least RB heads.
+// Row block g of a workgroup (g = wave * RB + rb, WG_BLOCKS of them, 16 rows each)
+// is head g % hpw of the workgroup's head group and token block g / hpw: the
+// heads of a KV group come first, so that a wavefront's row blocks share their
+// tokens (and their causal frontier) whenever the group has at least RB heads.
 
 // ------------------------------------------------------------------ phase 1
 // grid.x enumerates (kv head fastest, then work items); see launch_phase1_bf16.
-template <int RB>
-__global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1Args a, int hpw,
-                                                                           int tpb, int n_hs) {
+__global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1Args a, int hpw,
+                                                                          int tpb, int n_hs) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const Geom& g = a.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int half = lane >> 5, i32 = lane & 31;
-  const int tm = 32 * (NW * RB / hpw);           // tokens per workgroup
+  const int col = lane & 15, j4 = lane >> 4;
+  const int tm = 16 * (WG_BLOCKS / hpw);         // tokens per workgroup
 
   // work decode: kv head fastest (one KV head per XCD when Hkv is a multiple of
   // 8), then batch, head sub-group, tile within block (late = heavy first),
@@ -587,7 +590,7 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase1_bf16_kernel(P
 
   const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
-  WaveState<RB> w;
+  WaveState w;
   int head[RB], tok[RB], row_lim[RB];
   bool active[RB];
   int wave_lo = 0x7fffffff;
@@ -595,12 +598,13 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase1_bf16_kernel(P
   for (int rb = 0; rb < RB; ++rb) {
     int gb = wave * RB + rb;
     head[rb] = kvh * g.G + hs * hpw + gb % hpw;
-    int tok0 = row0 + 32 * (gb / hpw);
-    tok[rb] = tok0 + i32;
+    int tok0 = row0 + 16 * (gb / hpw);
+    tok[rb] = tok0 + col;
     active[rb] = tok[rb] < e;
     int qtok = active[rb] ? tok[rb] : (tok0 < e ? tok0 : e - 1);
-    load_q(w, rb, (const char*)a.Q + (((size_t)beta * g.L + qtok) * g.Hq + head[rb]) * ROWB, half);
-    // a row sees key k iff k < tok + 1; anchor keys always qualify (a <= b <= tok)
+    load_q(w, rb, (const char*)a.Q + (((size_t)beta * g.L + qtok) * g.Hq + head[rb]) * ROWB, j4);
+    // a row sees key k iff k < tok + 1; anchor keys always qualify (they precede
+    // the block or sit in their own buffer)
     row_lim[rb] = active[rb] ? tok[rb] + 1 : 0;
     int lo = tok0 < e ? tok0 + 1 : 0;
     wave_lo = lo < wave_lo ? lo : wave_lo;
@@ -625,24 +629,22 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase1_bf16_kernel(P
   seq.n_tiles = seq.n_a + (wg_last - s + TKEYS - 1) / TKEYS;
 
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend<RB>(w, seq, row_lim, wave_lo, g.scale * LOG2E, lds0);
+  attend(w, seq, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    float l_tot = pair_sum(w.l[rb]);
+    float l_tot = quad_sum(w.l[rb]);
     if (active[rb]) {
       float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
       char* orow = (char*)a.O + (((size_t)beta * g.L + tok[rb]) * g.Hq + head[rb]) * ROWB;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < 8; ++dt) {
+        bf16x4 v;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          bf16x4 v;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) v[k] = (__bf16)(w.o[rb][dt][4 * j + k] * inv);
-          *(bf16x4*)(orow + (32 * dt + 8 * j + 4 * half) * 2) = v;
-        }
-      if (a.LSE && half == 0)
+        for (int k = 0; k < 4; ++k) v[k] = (__bf16)(w.o[rb][dt][k] * inv);
+        *(bf16x4*)(orow + (16 * dt + 4 * j4) * 2) = v;
+      }
+      if (a.LSE && j4 == 0)
         a.LSE[((size_t)beta * g.Hq + head[rb]) * g.L + tok[rb]] =
             l_tot > 0.f ? (w.m[rb] * g.scale * LOG2E + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
     }
@@ -653,15 +655,14 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase1_bf16_kernel(P
 // Local attention (Eq. 1) and log-sum-exp (log of Eq. 2) of a row tile over one
 // split of the cache.  grid.x = ((batch * s_total + split) * n_hs + hs) * row_tiles + tile,
 // grid.y = kv head.
-template <int RB>
-__global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase2_rows_bf16_kernel(Phase2Args a, int hpw,
-                                                                                int n_hs,
-                                                                                int row_tiles) {
+__global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase2_rows_bf16_kernel(Phase2Args a, int hpw,
+                                                                               int n_hs,
+                                                                               int row_tiles) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const Geom& g = a.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int half = lane >> 5, i32 = lane & 31;
-  const int tm = 32 * (NW * RB / hpw);
+  const int col = lane & 15, j4 = lane >> 4;
+  const int tm = 16 * (WG_BLOCKS / hpw);
 
   int id = blockIdx.x;
   int tt = id % row_tiles; id /= row_tiles;
@@ -677,7 +678,7 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase2_rows_bf16_ker
 
   const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
-  WaveState<RB> w;
+  WaveState w;
   int head[RB], jrow[RB], row_lim[RB];
   bool active[RB];
   int wave_lo = 0x7fffffff;
@@ -686,11 +687,11 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase2_rows_bf16_ker
   for (int rb = 0; rb < RB; ++rb) {
     int gb = wave * RB + rb;
     head[rb] = kvh * g.G + hs * hpw + gb % hpw;
-    int j0 = tt * tm + 32 * (gb / hpw);
-    jrow[rb] = j0 + i32;
+    int j0 = tt * tm + 16 * (gb / hpw);
+    jrow[rb] = j0 + col;
     active[rb] = jrow[rb] < a.q_len;
     int qj = active[rb] ? jrow[rb] : (j0 < a.q_len ? j0 : a.q_len - 1);
-    load_q(w, rb, (const char*)a.Qq + (((size_t)beta * a.q_len + qj) * g.Hq + head[rb]) * ROWB, half);
+    load_q(w, rb, (const char*)a.Qq + (((size_t)beta * a.q_len + qj) * g.Hq + head[rb]) * ROWB, j4);
     // token j sees cache rows [0, cache_len + j]
     row_lim[rb] = active[rb] ? cl + jrow[rb] + 1 : 0;
     int l0 = j0 < a.q_len ? cl + j0 + 1 : 0;
@@ -705,25 +706,18 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase2_rows_bf16_ker
   seq.n_tiles = hi > lo ? (hi - lo + TKEYS - 1) / TKEYS : 0;
 
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  attend<RB>(w, seq, row_lim, wave_lo, g.scale * LOG2E, lds0);
+  attend(w, seq, row_lim, wave_lo, g.scale * LOG2E, lds0);
 
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    float l_tot = pair_sum(w.l[rb]);
+    float l_tot = quad_sum(w.l[rb]);
     if (active[rb]) {
       float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
       size_t r = (((size_t)beta * a.plan.s_total + sp) * g.Hq + head[rb]) * a.q_len + jrow[rb];
       float* orow = a.O_sub + r * D;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          f32x4 v;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) v[k] = w.o[rb][dt][4 * jj + k] * inv;
-          *(f32x4*)(orow + 32 * dt + 8 * jj + 4 * half) = v;
-        }
-      if (half == 0)
+      for (int dt = 0; dt < 8; ++dt) *(f32x4*)(orow + 16 * dt + 4 * j4) = w.o[rb][dt] * inv;
+      if (j4 == 0)
         a.LSE_sub[r] = l_tot > 0.f ? (w.m[rb] * g.scale * LOG2E + __builtin_amdgcn_logf(l_tot)) * LN2
                                    : -INFINITY;
     }
@@ -732,44 +726,46 @@ __global__ __launch_bounds__(NT, NW * RB == 4 ? 2 : 1) void phase2_rows_bf16_ker
 
 }  // namespace
 
-// Row blocks per wavefront of the two row-tiled kernels.
-constexpr int P1_RB = 1;
-constexpr int P2_RB = 1;
-
-// 32-row blocks per workgroup of the phase-2 row-tiled kernel (the split plan
-// sizes its grid with it).
-int flash_row_blocks() { return NW * P2_RB; }
+// Heads of one KV group that share a workgroup of the row-tiled kernels: the
+// largest of 8, 4, 2, 1 that divides G; the workgroup's 16-row blocks are split
+// evenly among them.
+int flash_heads_per_workgroup(int G) {
+  for (int h = 8; h > 1; h >>= 1)
+    if (h <= WG_BLOCKS && G % h == 0) return h;
+  return 1;
+}
+int flash_tokens_per_workgroup(int G) { return 16 * (WG_BLOCKS / flash_heads_per_workgroup(G)); }
 
 hipError_t launch_phase1_bf16(const Phase1Args& a, hipStream_t st) {
   const Geom& g = a.g;
-  int hpw = heads_per_workgroup(g.G, NW * P1_RB);
-  int tm = 32 * (NW * P1_RB / hpw);
+  int hpw = flash_heads_per_workgroup(g.G);
+  int tm = flash_tokens_per_workgroup(g.G);
   int n_hs = g.G / hpw;
   int64_t n = (g.L + g.b - 1) / g.b;
   int64_t bmax = g.b < g.L ? g.b : g.L;
   int tpb = (int)((bmax + tm - 1) / tm);
   int64_t wgs = (int64_t)g.Hkv * g.B * n_hs * tpb * n;
   if (wgs > 0x7fffffff) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute((const void*)phase1_bf16_kernel<P1_RB>,
+  hipError_t e = hipFuncSetAttribute((const void*)phase1_bf16_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
   if (e != hipSuccess) return e;
-  phase1_bf16_kernel<P1_RB><<<dim3((unsigned)wgs), NT, 4 * TILEB, st>>>(a, hpw, tpb, n_hs);
+  phase1_bf16_kernel<<<dim3((unsigned)wgs), NT, 4 * TILEB, st>>>(a, hpw, tpb, n_hs);
   return hipGetLastError();
 }
 
 hipError_t launch_phase2_rows_bf16(const Phase2Args& a, hipStream_t st) {
   const Geom& g = a.g;
-  int hpw = heads_per_workgroup(g.G, flash_row_blocks());
-  int tm = 32 * (flash_row_blocks() / hpw);
+  int hpw = flash_heads_per_workgroup(g.G);
+  int tm = flash_tokens_per_workgroup(g.G);
   int n_hs = g.G / hpw;
   int row_tiles = (a.q_len + tm - 1) / tm;
   int64_t gx = (int64_t)g.B * a.plan.s_total * n_hs * row_tiles;
   if (gx > 0x7fffffff || g.Hkv > 65535) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute((const void*)phase2_rows_bf16_kernel<P2_RB>,
+  hipError_t e = hipFuncSetAttribute((const void*)phase2_rows_bf16_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
   if (e != hipSuccess) return e;
-  phase2_rows_bf16_kernel<P2_RB><<<dim3((unsigned)gx, (unsigned)g.Hkv), NT, 4 * TILEB, st>>>(
-      a, hpw, n_hs, row_tiles);
+  phase2_rows_bf16_kernel<<<dim3((unsigned)gx, (unsigned)g.Hkv), NT, 4 * TILEB, st>>>(a, hpw, n_hs,
+                                                                                      row_tiles);
   return hipGetLastError();
 }
 
