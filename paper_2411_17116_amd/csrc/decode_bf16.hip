@@ -78,7 +78,7 @@ __device__ __forceinline__ float xor32_sum(float x) {
 }
 
 struct DecState {
-  bf16x8 q[4];     // Q^T fragments: q[t] = Q[column lane%16][32t + 8*(lane/16) .. +7]
+  bf16x8 q[4];     // Q^T fragments: q[t] = Q[column lane%16][32*(lane/16) + 8t .. +7]
   f32x4 o[8];      // O^T: o[dt][v] = O[column][16dt + 4*(lane/16) + v]
   float m, l;
 };
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
     const char* qrow = (const char*)a.Qq + (((size_t)beta * a.q_len + (live ? j : 0)) * g.Hq +
                                             (live ? head : kvh * g.G)) * ROWB;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) w.q[t] = *(const bf16x8*)(qrow + (32 * t + 8 * j4) * 2);
+    for (int t = 0; t < 4; ++t) w.q[t] = *(const bf16x8*)(qrow + (32 * j4 + 8 * t) * 2);
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) w.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     w.m = -INFINITY;
@@ -269,10 +269,12 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   }
 
   const unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  // K operand: lane (i = lane%16, j4) reads row i, chunk 4t + j4
+  // K operand: in MFMA step t, lane (i = lane%16, j4) reads row i, chunk 4 j4 + t
+  // (Q uses the same assignment of d-chunks; the transposed one, 4t + j4, costs
+  // LDS bank conflicts on these 16-byte reads)
   unsigned kaddr[4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) kaddr[t] = lds0 + qc * ROWB + (((4 * t + j4) ^ swz(qc)) << 4);
+  for (int t = 0; t < 4; ++t) kaddr[t] = lds0 + qc * ROWB + (((4 * j4 + t) ^ swz(qc)) << 4);
   // V^T operand: source lane addresses row 4*j4 + (lane%16)/4 (+16 for the second
   // read), columns 16dt + 4*(lane%4) .. +3
   unsigned vaddr[8];

@@ -146,7 +146,7 @@ struct TileSeq {
 // A wavefront's state.  Lane (col = lane % 16, j4 = lane / 16) belongs to query
 // row `col` of each of the wavefront's RB 16-row blocks.
 struct WaveState {
-  bf16x8 q[RB][4];    // Q^T fragments: q[rb][t] = Q[row col of block rb][32t + 8 j4 .. +7]
+  bf16x8 q[RB][4];    // Q^T fragments: q[rb][t] = Q[row col of block rb][32 j4 + 8t .. +7]
   f32x4 o[RB][8];     // O^T accumulators: o[rb][dt][v] = O[row][16 dt + 4 j4 + v]
   float m[RB];        // reference maximum of the raw logits (uniform over a row's four lanes)
   float neg_mc[RB];   // -m * c (0 while m == -inf)
@@ -156,7 +156,7 @@ struct WaveState {
 
 // Per-lane LDS addresses and DMA offsets, fixed for the whole kernel.
 struct LaneAddr {
-  unsigned k[4];       // K operand: row col, chunk 4t + j4 (swizzled)
+  unsigned k[4];       // K operand: row col, chunk 4 j4 + t (swizzled)
   unsigned v[8];       // V^T operand: see lane_addr()
   unsigned dma;        // byte offset of this thread's 16-byte unit in row tid/16
   int tid;
@@ -278,7 +278,7 @@ struct PreFrag {
   bf16x8 k[2], v[2];
 };
 
-// K fragment i = 4 kt + t of a 32-key unit: keys 16 kt .. +15, d 32 t .. +31.
+// K fragment i = 4 kt + t of a 32-key unit: keys 16 kt .. +15, MFMA step t.
 __device__ __forceinline__ bf16x8 read_k(const LaneAddr& la, int i, int off) {
   return lds_read_b128(la.k[i & 3] + off + (i >> 2) * 16 * ROWB);
 }
@@ -505,9 +505,12 @@ __device__ __forceinline__ LaneAddr lane_addr(unsigned lds0) {
   const int lane = la.tid & 63;
   const int col = lane & 15;
   la.j4 = lane >> 4;
-  // K operand: lane (col, j4) reads row col, chunk 4t + j4
+  // K operand: in MFMA step t, lane (col, j4) reads row col, chunk 4 j4 + t (any
+  // assignment of d-chunks to (t, j4) works as long as Q uses the same one; this
+  // one keeps the 16-byte reads of a wavefront free of LDS bank conflicts, the
+  // transposed one, 4t + j4, does not)
 #pragma unroll
-  for (int t = 0; t < 4; ++t) la.k[t] = lds0 + col * ROWB + (((4 * t + la.j4) ^ swz(col)) << 4);
+  for (int t = 0; t < 4; ++t) la.k[t] = lds0 + col * ROWB + (((4 * la.j4 + t) ^ swz(col)) << 4);
   // V^T operand: source lane addresses row 4 j4 + col/4 (+16 for the second
   // read), columns 16 dt + 4 (lane % 4) .. +3
   const int rr = 4 * la.j4 + (col >> 2);
@@ -553,7 +556,7 @@ __device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const i
 
 __device__ __forceinline__ void load_q(WaveState& w, int rb, const char* qrow, int j4) {
 #pragma unroll
-  for (int t = 0; t < 4; ++t) w.q[rb][t] = *(const bf16x8*)(qrow + (32 * t + 8 * j4) * 2);
+  for (int t = 0; t < 4; ++t) w.q[rb][t] = *(const bf16x8*)(qrow + (32 * j4 + 8 * t) * 2);
 }
 
 // Row block g of a workgroup (g = wave * RB + rb, WG_BLOCKS of them, 16 rows each)
