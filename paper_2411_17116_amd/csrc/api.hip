@@ -95,7 +95,7 @@ static bool make_plan(const star_attn_shape* s, int64_t q_len, int64_t total, bo
     // one thread walks a whole split in the fp32 kernel, so short calls are cut
     // much finer there (down to one 32-key LDS tile per split)
     const int64_t min_len = s->dtype == STAR_ATTN_F32 ? 32 : 256;
-    const int64_t want_wgs = s->dtype == STAR_ATTN_F32 ? 4096 : 1024;
+    const int64_t want_wgs = s->dtype == STAR_ATTN_F32 ? 4096 : 256;   // bf16: one workgroup per CU
     int64_t spb = ceil_div(want_wgs, wgs * n);
     int64_t spb_max = bmax / min_len > 1 ? bmax / min_len : 1;
     if (spb > spb_max) spb = spb_max;
