@@ -10,18 +10,20 @@
 // weight 0.  Under a flat split plan everything is one part.  The order of every
 // fold is fixed, so results are deterministic.
 //
-// One workgroup of 256 threads per (batch, head, row): eight groups of 32 lanes
-// walk the splits of a part, each lane owning d/32 output elements and each
-// group folding its splits with a running maximum (loads of four splits are in
-// flight per group); the eight partial results are combined through LDS.  Traffic is s_total * (d + 1) floats per row --
-// negligible next to the cache.
+// One workgroup per (batch, head, row): GROUPS groups of 32 lanes walk the
+// splits of a part, each lane owning d/32 output elements and each group
+// folding its splits with a running maximum (loads of INFL splits are in flight
+// per group); the partial results are combined through LDS.  A decode step has
+// few rows and hundreds of splits per row (16 groups x 8 in flight: four round
+// trips for 512 splits); a query-encode call has thousands of rows and a few
+// splits per part (8 groups x 4).  Traffic is s_total * (d + 1) floats per row
+// -- negligible next to the cache.
 #include "star_internal.h"
 
 namespace star {
 
 namespace {
 
-constexpr int GROUPS = 8;
 
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
   unsigned int u = __float_as_uint(f);
@@ -30,8 +32,8 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
   return (unsigned short)(u >> 16);
 }
 
-template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+template <int D, int GROUPS, int INFL>
+__global__ __launch_bounds__(32 * GROUPS) void merge_kernel(MergeArgs a) {
   constexpr int E = D / 32;                  // output elements per lane
   __shared__ float red_max[GROUPS];
   __shared__ float red_w[GROUPS];
@@ -58,18 +60,18 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     else if (m < p.n_blocks) { s_lo = m * p.spb; s_hi = s_lo + p.spb; }
     else { s_lo = p.n_blocks * p.spb; s_hi = p.s_total; }
 
-    // Each group folds its splits (s_lo + grp, + 8, ...) with a running maximum;
+    // Each group folds its splits (s_lo + grp, + GROUPS, ...) with a running maximum;
     // LSE and output loads of a split are independent of the fold, so several
     // splits are in flight at once.
     float pm = -INFINITY, wsum = 0.f;
     float acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = 0.f;
-    for (int s0 = s_lo + grp; s0 < s_hi; s0 += 4 * GROUPS) {
-      float ls[4];
-      float v[4][E];
+    for (int s0 = s_lo + grp; s0 < s_hi; s0 += INFL * GROUPS) {
+      float ls[INFL];
+      float v[INFL][E];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < INFL; ++u) {
         int s = s0 + u * GROUPS;
         ls[u] = -INFINITY;
         if (s < s_hi) {
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
         }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < INFL; ++u) {
         if (ls[u] == -INFINITY) continue;        // empty split: weight 0, output unset
         float m_new = fmaxf(pm, ls[u]);
         float sc_old = expf(pm - m_new);         // 0 for the first non-empty split
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
         pm = m_new;
       }
     }
-    // combine the eight groups: bring every group to the common maximum
+    // combine the groups: bring every group to the common maximum
     __syncthreads();                         // previous part's reads of red_* are done
     if (li == 0) red_max[grp] = pm;
     __syncthreads();
@@ -151,8 +153,10 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st) {
   int64_t rows = (int64_t)a.g.B * a.g.Hq * a.q_len;
-  if (a.g.d == 64) merge_kernel<64><<<dim3((unsigned)rows), 256, 0, st>>>(a);
-  else merge_kernel<128><<<dim3((unsigned)rows), 256, 0, st>>>(a);
+  const bool wide = a.plan.flat != 0;      // decode: few rows, hundreds of splits each
+  if (a.g.d == 64) merge_kernel<64, 8, 4><<<dim3((unsigned)rows), 256, 0, st>>>(a);
+  else if (wide) merge_kernel<128, 16, 8><<<dim3((unsigned)rows), 512, 0, st>>>(a);
+  else merge_kernel<128, 8, 4><<<dim3((unsigned)rows), 256, 0, st>>>(a);
   return hipGetLastError();
 }
 
