@@ -129,10 +129,10 @@ int star_attn_phase1(const star_attn_shape* shape,
  *
  *   K_anchor, V_anchor  in  [B, a, Hkv, d], dtype of the inputs; read only in
  *                 mode EXTERNAL with a > 0 (else may be NULL)
- *   workspace     mode EXTERNAL: at least
- *                 star_attn_phase1_workspace_bytes(shape, mode) bytes, 256-byte
- *                 aligned (holds a head-major copy of the anchor; scratch);
- *                 other modes: unused, may be NULL / 0
+ *   workspace     at least star_attn_phase1_workspace_bytes(shape, mode) bytes,
+ *                 256-byte aligned, scratch (only mode EXTERNAL with fp32 tensors
+ *                 needs any: a head-major copy of the anchor); unused and may be
+ *                 NULL / 0 when that size is 0
  *   other arguments as in star_attn_phase1
  * Errors as in star_attn_phase1, plus STAR_ATTN_ERR_INVALID_MODE and
  * STAR_ATTN_ERR_WORKSPACE_TOO_SMALL.
@@ -144,7 +144,7 @@ int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode,
                             void* K_cache, void* V_cache,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Workspace bytes star_attn_phase1_anchor needs (0 unless mode EXTERNAL; 0 for an invalid shape). */
+/* Workspace bytes star_attn_phase1_anchor needs (0 unless mode EXTERNAL with fp32; 0 for an invalid shape). */
 size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode);
 
 /*

@@ -175,7 +175,8 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
 
 size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode) {
   if (validate_shape(shape) != STAR_ATTN_OK) return 0;
-  return anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ? 2 * anchor_copy_bytes(shape) : 0;
+  return anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL && shape->dtype == STAR_ATTN_F32
+             ? 2 * anchor_copy_bytes(shape) : 0;
 }
 
 }  // extern "C"
@@ -197,16 +198,27 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
       misaligned(K_cache) || misaligned(V_cache) || ((uintptr_t)LSE_ctx & 3u))
     return STAR_ATTN_ERR_MISALIGNED;
   const bool ext = anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL && shape->anchor > 0;
+  // the fp32 kernel reads a head-major copy of the external anchor (workspace);
+  // the bf16 kernel reads the caller's tensors directly
+  const bool ext_copy = ext && shape->dtype == STAR_ATTN_F32;
   if (ext) {
-    if (!K_anchor || !V_anchor || !workspace) return STAR_ATTN_ERR_NULL_POINTER;
-    if (misaligned(K_anchor) || misaligned(V_anchor) || ((uintptr_t)workspace & 255u))
-      return STAR_ATTN_ERR_MISALIGNED;
+    if (!K_anchor || !V_anchor) return STAR_ATTN_ERR_NULL_POINTER;
+    if (misaligned(K_anchor) || misaligned(V_anchor)) return STAR_ATTN_ERR_MISALIGNED;
+  }
+  if (ext_copy) {
+    if (!workspace) return STAR_ATTN_ERR_NULL_POINTER;
+    if ((uintptr_t)workspace & 255u) return STAR_ATTN_ERR_MISALIGNED;
     if (workspace_bytes < 2 * anchor_copy_bytes(shape)) return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
   }
   Geom g = make_geom(shape);
   hipStream_t st = (hipStream_t)hip_stream;
   // Algorithm 1: keep the K/V of every block once (anchor copies never exist here).
-  if (rope) {
+  // The bf16 attention kernel reads plain inputs where they are and files them in
+  // the caches itself; rotated keys and the fp32 kernel go through the caches.
+  const bool fused_cache_write = shape->dtype == STAR_ATTN_BF16 && !rope;
+  if (fused_cache_write) {
+    // nothing to launch here
+  } else if (rope) {
     if (launch_rope_rotate(shape->dtype, g.B, g.L, g.Hq, g.d, rope->pos0, rope->theta, Q, Q, st) !=
             hipSuccess ||
         launch_rope_cache_write(g, shape->dtype, K, K_cache, g.L, 0, rope->pos0, rope->theta, st) !=
@@ -218,8 +230,10 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
   }
   Phase1Args a;
   a.g = g; a.Q = Q; a.O = O_ctx; a.LSE = LSE_ctx; a.Kc = K_cache; a.Vc = V_cache;
-  a.anchor_mode = anchor_mode; a.Ka = nullptr; a.Va = nullptr;
-  if (ext) {
+  a.anchor_mode = anchor_mode; a.Ka = K_anchor; a.Va = V_anchor;
+  a.Kin = fused_cache_write ? K : nullptr;
+  a.Vin = fused_cache_write ? V : nullptr;
+  if (ext_copy) {
     // the separately given anchor, head-major like the caches: [B, Hkv, a, d]
     Geom ga = g;
     ga.cap = g.a;

@@ -123,7 +123,9 @@ __device__ __forceinline__ void wait_vmcnt_2tiles() {
 
 // Sequence of key tiles a workgroup walks: first the tiles of the anchor rows
 // [a_lo, a_hi) of Ka / Va (n_a of them), then the tiles of rows [loc_lo, loc_hi)
-// of Kl / Vl.  All four are bases of one (batch, KV head), rows of ROWB bytes.
+// of Kl / Vl.  All four are bases of one (batch, KV head); consecutive key rows
+// are a_stride / l_stride bytes apart (ROWB in a head-major cache, Hkv * ROWB in
+// a token-major input tensor).
 struct TileSeq {
   int n_a;
   int n_tiles;
@@ -135,6 +137,9 @@ struct TileSeq {
   const char* Va;
   const char* Kl;
   const char* Vl;
+  int a_stride;
+  int l_stride;
+  __device__ __forceinline__ int stride(int idx) const { return idx < n_a ? a_stride : l_stride; }
   __device__ __forceinline__ void tile(int idx, int* key0, int* hi) const {
     if (idx < n_a) { *key0 = a_lo + idx * TKEYS; *hi = a_hi; }
     else { *key0 = loc_lo + (idx - n_a) * TKEYS; *hi = loc_hi; }
@@ -158,7 +163,7 @@ struct WaveState {
 struct LaneAddr {
   unsigned k[4];       // K operand: row col, chunk 4 j4 + t (swizzled)
   unsigned v[8];       // V^T operand: see lane_addr()
-  unsigned dma;        // byte offset of this thread's 16-byte unit in row tid/16
+  unsigned dma;        // byte offset of this thread's 16-byte unit inside its key row
   int tid;
   int j4;
 };
@@ -167,21 +172,21 @@ struct LaneAddr {
 // `tid` moves the 16-byte unit (row it*DMA_ROWS + tid/16, slot tid%16) for each it;
 // rows at or past `hi` re-read the last valid row (they are masked in the score
 // tile, and finite values keep 0 * V finite).
-__device__ __forceinline__ void issue_tile(const char* base, int key0, int hi, unsigned lds,
-                                           const LaneAddr& la) {
+__device__ __forceinline__ void issue_tile(const char* base, int stride, int key0, int hi,
+                                           unsigned lds, const LaneAddr& la) {
   unsigned wave_base = __builtin_amdgcn_readfirstlane((la.tid & ~63) * 16);
-  if (key0 + TKEYS <= hi) {            // full tile: scalar base, constant lane offsets
-    const char* sb = base + (size_t)key0 * ROWB;
+  if (key0 + TKEYS <= hi) {            // full tile: scalar base, loop-invariant lane offsets
+    const char* sb = base + (size_t)key0 * stride;
+    const unsigned voff = (unsigned)(la.tid >> 4) * stride + la.dma;
 #pragma unroll
     for (int it = 0; it < DMA_ITERS; ++it)
-      dma16(sb + it * DMA_ROWS * ROWB, la.dma, lds + it * DMA_ROWS * ROWB + wave_base);
+      dma16(sb + (size_t)(it * DMA_ROWS) * stride, voff, lds + it * DMA_ROWS * ROWB + wave_base);
   } else {
-    int chunk_off = la.dma & 255;
 #pragma unroll
     for (int it = 0; it < DMA_ITERS; ++it) {
       int key = key0 + it * DMA_ROWS + (la.tid >> 4);
       key = key < hi ? key : hi - 1;
-      dma16(base, (unsigned)key * ROWB + chunk_off, lds + it * DMA_ROWS * ROWB + wave_base);
+      dma16(base, (unsigned)key * (unsigned)stride + la.dma, lds + it * DMA_ROWS * ROWB + wave_base);
     }
   }
 }
@@ -410,12 +415,12 @@ __device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, cons
   if (t + 2 < seq.n_tiles) {
     int k2, h2;
     seq.tile(t + 2, &k2, &h2);
-    issue_tile(seq.kbase(t + 2), k2, h2, lds0 + KF, la);
+    issue_tile(seq.kbase(t + 2), seq.stride(t + 2), k2, h2, lds0 + KF, la);
   }
   if (MORE) {
     int nk0, nhi;
     seq.tile(t + 1, &nk0, &nhi);
-    issue_tile(seq.vbase(t + 1), nk0, nhi, lds0 + VF, la);
+    issue_tile(seq.vbase(t + 1), seq.stride(t + 1), nk0, nhi, lds0 + VF, la);
     stage<SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB, r.pA,
                                                                        c, alpha, pre);
     if (SAFE) rescale(w, alpha);
@@ -448,12 +453,12 @@ __device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const
 
   // Prologue: K tile 0, V tile 0 and K tile 1 in flight; scores of tile 0.
   seq.tile(0, &key0, &hi);
-  issue_tile(seq.kbase(0), key0, hi, lds0 + K0, la);
-  issue_tile(seq.vbase(0), key0, hi, lds0 + V0, la);
+  issue_tile(seq.kbase(0), seq.stride(0), key0, hi, lds0 + K0, la);
+  issue_tile(seq.vbase(0), seq.stride(0), key0, hi, lds0 + V0, la);
   if (T > 1) {
     int k1, h1;
     seq.tile(1, &k1, &h1);
-    issue_tile(seq.kbase(1), k1, h1, lds0 + K1, la);
+    issue_tile(seq.kbase(1), seq.stride(1), k1, h1, lds0 + K1, la);
     wait_vmcnt_2tiles();
   } else {
     wait_vmcnt0();
@@ -517,8 +522,7 @@ __device__ __forceinline__ LaneAddr lane_addr(unsigned lds0) {
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt)
     la.v[dt] = lds0 + rr * ROWB + (((2 * dt + ((lane & 3) >> 1)) ^ swz(rr)) << 4) + 8 * (lane & 1);
-  unsigned chunk_off = ((la.tid & 15) ^ swz(la.tid >> 4)) << 4;
-  la.dma = (la.tid >> 4) * ROWB + chunk_off;
+  la.dma = ((la.tid & 15) ^ swz(la.tid >> 4)) << 4;
   return la;
 }
 
@@ -591,8 +595,17 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1
   if (row0 >= e) return;                         // tile beyond a short block
   int wg_last = row0 + tm < e ? row0 + tm : e;   // exclusive bound of the workgroup's tokens
 
-  const char* Kb = (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
-  const char* Vb = (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
+  // K / V rows of this (batch, KV head): from the token-major inputs when the
+  // call hands them over as they are (then this kernel also files them in the
+  // cache), else from the head-major caches a preceding kernel has filled
+  const bool from_input = a.Kin != nullptr;
+  const int kv_stride = from_input ? g.Hkv * ROWB : ROWB;
+  const char* Kb = from_input
+      ? (const char*)a.Kin + ((size_t)beta * g.L * g.Hkv + kvh) * ROWB
+      : (const char*)a.Kc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
+  const char* Vb = from_input
+      ? (const char*)a.Vin + ((size_t)beta * g.L * g.Hkv + kvh) * ROWB
+      : (const char*)a.Vc + ((size_t)beta * g.Hkv + kvh) * (size_t)g.cap * ROWB;
   WaveState w;
   int head[RB], tok[RB], row_lim[RB];
   bool active[RB];
@@ -622,10 +635,12 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1
   const bool ext = anchor_range(g, a.anchor_mode, i, &a_lo, &a_hi);
   seq.a_lo = (int)a_lo;
   seq.a_hi = (int)a_hi;
-  seq.Ka = ext ? (const char*)a.Ka + ((size_t)beta * g.Hkv + kvh) * (size_t)g.a * ROWB : Kb;
-  seq.Va = ext ? (const char*)a.Va + ((size_t)beta * g.Hkv + kvh) * (size_t)g.a * ROWB : Vb;
+  seq.Ka = ext ? (const char*)a.Ka + ((size_t)beta * g.a * g.Hkv + kvh) * ROWB : Kb;
+  seq.Va = ext ? (const char*)a.Va + ((size_t)beta * g.a * g.Hkv + kvh) * ROWB : Vb;
   seq.Kl = Kb;
   seq.Vl = Vb;
+  seq.l_stride = kv_stride;
+  seq.a_stride = ext ? g.Hkv * ROWB : kv_stride;
   seq.n_a = (seq.a_hi - seq.a_lo + TKEYS - 1) / TKEYS;
   seq.loc_lo = s;
   seq.loc_hi = wg_last;
@@ -650,6 +665,22 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1
       if (a.LSE && j4 == 0)
         a.LSE[((size_t)beta * g.Hq + head[rb]) * g.L + tok[rb]] =
             l_tot > 0.f ? (w.m[rb] * g.scale * LOG2E + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
+    }
+  }
+
+  // Algorithm 1, "keep the block's K/V": the workgroup files the K and V rows of
+  // its own tokens in the head-major caches (they were among the last tiles it
+  // streamed, so these reads hit in L2).  One head sub-group per token range does it.
+  if (from_input && hs == 0) {
+    const int n_units = (wg_last - row0) * 16;            // 16-byte units per tensor
+    char* kc = (char*)a.Kc + (((size_t)beta * g.Hkv + kvh) * (size_t)g.cap + row0) * ROWB;
+    char* vc = (char*)a.Vc + (((size_t)beta * g.Hkv + kvh) * (size_t)g.cap + row0) * ROWB;
+    for (int u = tid; u < n_units; u += NT) {
+      size_t src = (size_t)(row0 + (u >> 4)) * kv_stride + (u & 15) * 16;
+      i32x4 kx = *(const i32x4*)(Kb + src);
+      i32x4 vx = *(const i32x4*)(Vb + src);
+      *(i32x4*)(kc + (size_t)u * 16) = kx;
+      *(i32x4*)(vc + (size_t)u * 16) = vx;
     }
   }
 }
@@ -706,6 +737,7 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase2_rows_bf16_kernel(P
   TileSeq seq;
   seq.a_lo = 0; seq.a_hi = 0; seq.n_a = 0; seq.loc_lo = lo; seq.loc_hi = hi;
   seq.Ka = Kb; seq.Va = Vb; seq.Kl = Kb; seq.Vl = Vb;
+  seq.a_stride = ROWB; seq.l_stride = ROWB;
   seq.n_tiles = hi > lo ? (hi - lo + TKEYS - 1) / TKEYS : 0;
 
   unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;

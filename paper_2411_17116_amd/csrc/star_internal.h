@@ -50,8 +50,10 @@ struct Phase1Args {
   const void* Kc;       // caches [B, Hkv, cap, d], already holding the context
   const void* Vc;
   int32_t anchor_mode;  // AnchorMode
-  const void* Ka;       // ANCHOR_EXTERNAL: anchor keys / values, head-major
-  const void* Va;       // [B, Hkv, a, d]; otherwise unused
+  const void* Ka;       // ANCHOR_EXTERNAL: anchor keys / values; head-major [B, Hkv, a, d]
+  const void* Va;       // for the fp32 kernel, token-major [B, a, Hkv, d] for the bf16 one
+  const void* Kin;      // bf16 kernel: the token-major inputs [B, L, Hkv, d] to read keys /
+  const void* Vin;      // values from (and to file in the caches); null: read the caches
 };
 
 // Anchor key rows [*lo, *hi) of 0-based block i, and whether they index the

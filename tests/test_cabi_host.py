@@ -168,18 +168,22 @@ def test_phase1_anchor_variant_arguments(lib):
     for mode in (binding.ANCHOR_FIRST, binding.ANCHOR_PREVIOUS, EXT):
         assert _p1a(lib, shape, mode, Q=None) == ERR["NULL_POINTER"]
         assert _p1a(lib, shape, mode, Kc=0x1004) == ERR["MISALIGNED"]
-    # the external anchor needs its tensors and a workspace for their head-major copy
-    need = sa.binding.phase1_workspace_bytes(shape, EXT)
-    assert need == 2 * 1 * 2 * 256 * 128 * 2 and need % 256 == 0
-    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_FIRST) == 0
-    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_PREVIOUS) == 0
+    # the external anchor needs its tensors; the fp32 path also needs a workspace
+    # for their head-major copy (the bf16 kernel reads the tensors where they are)
+    assert sa.binding.phase1_workspace_bytes(shape, EXT) == 0
+    assert _p1a(lib, shape, EXT, Ka=None) == ERR["NULL_POINTER"]
+    assert _p1a(lib, shape, EXT, Va=None) == ERR["NULL_POINTER"]
+    assert _p1a(lib, shape, EXT, Ka=0x1008) == ERR["MISALIGNED"]
+    f32 = good_shape(dtype="fp32", head_dim=64)
+    need = sa.binding.phase1_workspace_bytes(f32, EXT)
+    assert need == 2 * 1 * 2 * 256 * 64 * 4 and need % 256 == 0
+    assert sa.binding.phase1_workspace_bytes(f32, binding.ANCHOR_FIRST) == 0
+    assert sa.binding.phase1_workspace_bytes(f32, binding.ANCHOR_PREVIOUS) == 0
     assert sa.binding.phase1_workspace_bytes(good_shape(batch=0), EXT) == 0
-    assert _p1a(lib, shape, EXT, Ka=None, ws_bytes=need) == ERR["NULL_POINTER"]
-    assert _p1a(lib, shape, EXT, Va=None, ws_bytes=need) == ERR["NULL_POINTER"]
-    assert _p1a(lib, shape, EXT, ws=None, ws_bytes=need) == ERR["NULL_POINTER"]
-    assert _p1a(lib, shape, EXT, Ka=0x1008, ws_bytes=need) == ERR["MISALIGNED"]
-    assert _p1a(lib, shape, EXT, ws=0x1010, ws_bytes=need) == ERR["MISALIGNED"]
-    assert _p1a(lib, shape, EXT, ws_bytes=need - 1) == ERR["WORKSPACE_TOO_SMALL"]
+    assert _p1a(lib, f32, EXT, Ka=None, ws_bytes=need) == ERR["NULL_POINTER"]
+    assert _p1a(lib, f32, EXT, ws=None, ws_bytes=need) == ERR["NULL_POINTER"]
+    assert _p1a(lib, f32, EXT, ws=0x1010, ws_bytes=need) == ERR["MISALIGNED"]
+    assert _p1a(lib, f32, EXT, ws_bytes=need - 1) == ERR["WORKSPACE_TOO_SMALL"]
 
 
 def test_rope_entry_point_arguments(lib):
