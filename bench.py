@@ -4,8 +4,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C3]
 
 One "step" is one pass of the whole hot path over one synthetic batch of the
-chosen configuration: phase 1 over the context (KV-cache write + anchor-block
-attention), the phase-2 query-encoding call, and every decode step.  Inputs are
+chosen configuration: phase 1 over the context (anchor-block attention + KV-cache
+write), the phase-2 query-encoding call, and every decode step.  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line:
 
   value / unit        phase-1 context tokens per second (B * L / phase-1 time)
@@ -423,8 +423,8 @@ def main():
                      "achieved": p1_tflops, "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
                      "unit": "TFLOP/s", "frac": p1_tflops / MFMA_PEAK_TFLOPS[cfg.dtype],
                      "traffic": measured_traffic("phase1", cfg.name),
-                     "note": "flops = 4 d per visible (query, key) pair; time = phase-1 call "
-                             "(KV-cache write + attention kernel)"},
+                     "note": "flops = 4 d per visible (query, key) pair; time = the phase-1 call "
+                             "(bf16: one kernel that attends and files K/V in the caches)"},
         "roofline_decode": {"bound": "hbm", "kernel": "decode_bf16_kernel" if cfg.dtype == "bf16" else "phase2_f32_kernel",
                             "achieved": dec_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": dec_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("decode", cfg.name),
