@@ -181,12 +181,13 @@ __device__ __forceinline__ void issue_tile(const char* base, int stride, int key
 #pragma unroll
     for (int it = 0; it < DMA_ITERS; ++it)
       dma16(sb + (size_t)(it * DMA_ROWS) * stride, voff, lds + it * DMA_ROWS * ROWB + wave_base);
-  } else {
+  } else {                             // ragged tile: clamp each lane's row below hi
+    const char* sb = base + (size_t)key0 * stride;
 #pragma unroll
     for (int it = 0; it < DMA_ITERS; ++it) {
-      int key = key0 + it * DMA_ROWS + (la.tid >> 4);
-      key = key < hi ? key : hi - 1;
-      dma16(base, (unsigned)key * (unsigned)stride + la.dma, lds + it * DMA_ROWS * ROWB + wave_base);
+      int row = it * DMA_ROWS + (la.tid >> 4);
+      row = key0 + row < hi ? row : hi - 1 - key0;
+      dma16(sb, (unsigned)row * (unsigned)stride + la.dma, lds + it * DMA_ROWS * ROWB + wave_base);
     }
   }
 }
