@@ -75,7 +75,8 @@ typedef struct star_attn_shape {
   int64_t ctx_len;        /* L: context tokens */
   int64_t block;          /* b >= 1: block size; n = ceil(L / b) blocks, the last may be short */
   int64_t anchor;         /* a in [0, b]: the first a context tokens prefix every block but the first */
-  int64_t cache_capacity; /* rows per (batch, KV head) in the caches: >= L + every later append */
+  int64_t cache_capacity; /* rows per (batch, KV head) in the caches: >= L + every later append;
+                             below 2^31 - 2^20 (as is block) */
   float   softmax_scale;  /* 0 selects 1/sqrt(d) (Eq. 1) */
   float   reserved2;      /* set to 0 */
 } star_attn_shape;

@@ -16,6 +16,9 @@ static int validate_shape(const star_attn_shape* s) {
     return STAR_ATTN_ERR_INVALID_SHAPE;
   if (s->n_q_heads % s->n_kv_heads != 0) return STAR_ATTN_ERR_INVALID_SHAPE;
   if (s->n_q_heads > 65535 || s->batch > 65535) return STAR_ATTN_ERR_INVALID_SHAPE;
+  // the kernels index tokens with 32-bit integers
+  if (s->cache_capacity > (int64_t)0x7ff00000 || s->block > (int64_t)0x7ff00000)
+    return STAR_ATTN_ERR_INVALID_SHAPE;
   if (s->dtype == STAR_ATTN_F32) {
     if (s->head_dim != 64 && s->head_dim != 128) return STAR_ATTN_ERR_UNSUPPORTED_HEAD_DIM;
   } else {

@@ -95,6 +95,8 @@ def _p2(lib, shape, cache_len, q_len, Qq=0x1000, Kq=0x1000, Vq=0x1000, Kc=0x1000
     (dict(anchor=-1), "ANCHOR_GT_BLOCK"),
     (dict(cache_capacity=1000), "CACHE_OVERFLOW"),
     (dict(softmax_scale=-1.0), "INVALID_SHAPE"),
+    (dict(cache_capacity=1 << 31), "INVALID_SHAPE"),       # tokens are indexed with 32 bits
+    (dict(block=1 << 32, anchor=0), "INVALID_SHAPE"),
 ])
 def test_bad_shapes_are_rejected_by_both_entry_points(lib, kw, code):
     shape = good_shape(**kw)
