@@ -94,3 +94,25 @@ def test_run_to_run_determinism():
         outs.append((run.O_ctx.clone(), run.LSE_ctx.clone(), O, Op, Lp, O1))
     for x, y in zip(*outs):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("Hq,Hkv,lq", [(4, 1, 4), (4, 2, 5), (8, 1, 2), (6, 2, 3), (1, 1, 16)])
+def test_decode_sized_calls_with_several_new_tokens(Hq, Hkv, lq):
+    """G * q_len <= 16 rows per KV head take the streaming split-KV kernel even
+    when the call brings more than one token (speculative / chunked decoding):
+    the new tokens attend causally among themselves.  With and without per-part
+    outputs (block-aligned and flat split plans)."""
+    cfg = workloads.StarConfig("multitok", "bf16", 2, Hq, Hkv, 128, 3000, 1024, 300, lq, 3,
+                               seed=Hq * 10 + lq, n_planted=4)
+    rep = ph.run_parity(cfg, all_rows=True)          # query call and decode steps, per-part outputs
+    _report(rep)
+    # the same query call without per-part outputs (flat plan) must give the same O
+    inp = workloads.make_inputs(cfg, "cuda")
+    r1, r2 = ph.HipRun(cfg, inp, "cuda"), ph.HipRun(cfg, inp, "cuda")
+    r1.phase1()
+    r2.phase1()
+    O1, _, _ = r1.phase2(inp.Qq, inp.Kq, inp.Vq, want_parts=True)
+    O2, _, _ = r2.phase2(inp.Qq, inp.Kq, inp.Vq, want_parts=False)
+    torch.cuda.synchronize()
+    assert (O1.float() - O2.float()).abs().max().item() <= 2e-2
+    assert torch.equal(r1.Kc, r2.Kc) and torch.equal(r1.Vc, r2.Vc)
