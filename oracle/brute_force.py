@@ -52,12 +52,14 @@ def external_anchor_dense(Q, K, V, Ka, Va, b: int, scale=None):
     """Phase 1 with separately given anchor keys/values, by brute force: for
     every block after the first, lay out the sequence [anchor; block] as Figure 2
     draws it, run dense causal-within-[anchor; block] attention with an explicit
-    mask, and keep the rows of the block.  Ka, Va [B, a, Hkv, d].
+    mask, and keep the rows of the block.  Ka, Va [B, a, Hkv, d], or
+    [B, n, a, Hkv, d] for one anchor per block (block i uses slice i).
     Returns O [B, L, Hq, d], LSE [B, Hq, L]."""
     B, L, Hq, d = Q.shape
     Hkv = K.shape[2]
     G = Hq // Hkv
-    a = Ka.shape[1]
+    per_block = Ka.ndim == 5
+    a = Ka.shape[2] if per_block else Ka.shape[1]
     sc = 1.0 / math.sqrt(d) if scale is None else scale
     n = -(-L // b)
     O = np.zeros((B, L, Hq, d))
@@ -69,8 +71,10 @@ def external_anchor_dense(Q, K, V, Ka, Va, b: int, scale=None):
                 s, e = i * b, min((i + 1) * b, L)
                 rows = e - s
                 pre = 0 if i == 0 else a
-                kk = K[beta, s:e, g] if i == 0 else np.concatenate([Ka[beta, :, g], K[beta, s:e, g]])
-                vv = V[beta, s:e, g] if i == 0 else np.concatenate([Va[beta, :, g], V[beta, s:e, g]])
+                ka = Ka[beta, i, :, g] if per_block else Ka[beta, :, g]
+                va = Va[beta, i, :, g] if per_block else Va[beta, :, g]
+                kk = K[beta, s:e, g] if i == 0 else np.concatenate([ka, K[beta, s:e, g]])
+                vv = V[beta, s:e, g] if i == 0 else np.concatenate([va, V[beta, s:e, g]])
                 mask = np.zeros((rows, pre + rows), dtype=bool)
                 for r in range(rows):
                     mask[r, :pre + r + 1] = True

@@ -211,6 +211,8 @@ ANCHOR_FIRST = 0      # the method itself: first `a` tokens of block 1
 ANCHOR_PREVIOUS = 1   # "previous block as anchor": the `a` tokens just before the block
 ANCHOR_EXTERNAL = 2   # anchor keys/values given separately (other content, or the
                       # first block's content encoded at other position ids)
+ANCHOR_PER_BLOCK = 3  # a separately given anchor for every block (position ids that
+                      # follow the block, e.g. "same as previous block")
 
 
 def anchor_key_rows(i: int, b: int, a: int, mode: int) -> np.ndarray:
@@ -228,7 +230,9 @@ def phase1_row_variant(Q, K, V, beta: int, h: int, p: int, b: int, a: int, mode:
                        ) -> Tuple[np.ndarray, float]:
     """Phase-1 row under an anchor variant.  The row attends to the anchor's
     `a` keys (all visible) followed by its own block up to itself; for
-    ANCHOR_EXTERNAL the anchor keys/values are K_anchor, V_anchor [B, a, Hkv, d]."""
+    ANCHOR_EXTERNAL the anchor keys/values are K_anchor, V_anchor [B, a, Hkv, d];
+    for ANCHOR_PER_BLOCK they are [B, n, a, Hkv, d] and 0-based block i uses slice i
+    (slice 0 is never read: block 1 has no anchor)."""
     B, L, Hq, d = Q.shape
     Hkv = K.shape[2]
     g = h // (Hq // Hkv)
@@ -240,6 +244,12 @@ def phase1_row_variant(Q, K, V, beta: int, h: int, p: int, b: int, a: int, mode:
     sc = softmax_scale(d, scale)
     if i == 0:
         return attend(Q[beta, p, h], K[beta, own, g], V[beta, own, g], sc)
+    if mode == ANCHOR_PER_BLOCK:
+        if K_anchor.shape[1] != num_blocks(L, b) or K_anchor.shape[2] != a:
+            raise ValueError("per-block anchors must be [B, n, a, Hkv, d]")
+        Kv = np.concatenate([np.asarray(K_anchor[beta, i, :, g], F64), np.asarray(K[beta, own, g], F64)])
+        Vv = np.concatenate([np.asarray(V_anchor[beta, i, :, g], F64), np.asarray(V[beta, own, g], F64)])
+        return attend(Q[beta, p, h], Kv, Vv, sc)
     if mode == ANCHOR_EXTERNAL:
         if K_anchor.shape[1] != a or V_anchor.shape[1] != a:
             raise ValueError("external anchor must hold exactly `a` tokens")

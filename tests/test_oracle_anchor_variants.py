@@ -125,3 +125,64 @@ def test_a_shifted_anchor_window_is_caught():
     ks = np.concatenate([np.arange(2 * b - a - 1, 2 * b - 1), np.arange(2 * b, p + 1)])
     o_bad, _ = so.attend(Q[0, p, 0], K[0, ks, 0], V[0, ks, 0], 0.5)
     assert np.abs(o_bad - o_ref[p]).max() > 1e-6
+
+
+@pytest.mark.parametrize("B,L,Hq,Hkv,d,b,a", SHAPES)
+def test_per_block_anchors_match_brute_force(B, L, Hq, Hkv, d, b, a):
+    Q, K, V = rand_qkv(B, L, Hq, Hkv, d)
+    n = -(-L // b)
+    Ka = RNG.standard_normal((B, n, a, Hkv, d))
+    Va = RNG.standard_normal((B, n, a, Hkv, d))
+    O, LSE = so.phase1_full_variant(Q, K, V, b, a, so.ANCHOR_PER_BLOCK, Ka, Va)
+    Ob, LSEb = bf.external_anchor_dense(Q, K, V, Ka, Va, b)
+    assert np.abs(O - Ob).max() < TOL
+    assert np.abs(LSE - LSEb).max() < TOL
+
+
+def test_per_block_anchors_that_are_all_alike_are_one_external_anchor():
+    B, L, Hq, Hkv, d, b, a = 1, 26, 2, 1, 8, 7, 4
+    Q, K, V = rand_qkv(B, L, Hq, Hkv, d)
+    Ka = RNG.standard_normal((B, a, Hkv, d))
+    Va = RNG.standard_normal((B, a, Hkv, d))
+    n = -(-L // b)
+    O1, L1 = so.phase1_full_variant(Q, K, V, b, a, so.ANCHOR_EXTERNAL, Ka, Va)
+    O2, L2 = so.phase1_full_variant(Q, K, V, b, a, so.ANCHOR_PER_BLOCK,
+                                    np.repeat(Ka[:, None], n, axis=1), np.repeat(Va[:, None], n, axis=1))
+    assert np.array_equal(O1, O2) and np.array_equal(L1, L2)
+
+
+def test_position_id_ablation_composes_from_rotation_and_per_block_anchors():
+    """Section 4.1, "position IDs same as previous block": the anchor keeps the
+    first block's content but is encoded at the positions just before each
+    block.  Composed here from the rotation and per-block anchors, and checked
+    against a brute force that lays out [anchor at those positions; block]
+    explicitly.  With rotary embeddings logits depend on position differences
+    only, so this anchor is the first block seen from a = b tokens away."""
+    B, L, Hq, Hkv, d, b, theta = 1, 24, 2, 1, 8, 8, 10000.0
+    a = b
+    Qp, Kp, V = rand_qkv(B, L, Hq, Hkv, d)            # unrotated projections
+    pos = np.arange(L)
+    Q = so.rope_rotate(Qp, pos, theta)
+    K = so.rope_rotate(Kp, pos, theta)
+    n = L // b
+    Ka = np.zeros((B, n, a, Hkv, d))
+    Va = np.zeros((B, n, a, Hkv, d))
+    for i in range(1, n):
+        Ka[:, i] = so.rope_rotate(Kp[:, :a], i * b - a + np.arange(a), theta)   # ids of the previous block
+        Va[:, i] = V[:, :a]
+    O, LSE = so.phase1_full_variant(Q, K, V, b, a, so.ANCHOR_PER_BLOCK, Ka, Va)
+    # brute force: block i attends [first block's tokens at positions s-a..s-1 ; its own tokens]
+    for i in range(1, n):
+        s = i * b
+        for h in range(Hq):
+            kk = np.concatenate([Ka[0, i, :, 0], K[0, s:s + b, 0]])
+            vv = np.concatenate([V[0, :a, 0], V[0, s:s + b, 0]])
+            mask = np.zeros((b, a + b), dtype=bool)
+            for r in range(b):
+                mask[r, :a + r + 1] = True
+            o, l = bf.dense_masked_attention(Q[0, s:s + b, h], kk, vv, mask, 1.0 / np.sqrt(d))
+            assert np.abs(O[0, s:s + b, h] - o).max() < 1e-10
+            assert np.abs(LSE[0, h, s:s + b] - l).max() < 1e-10
+    # ... and it differs from the method itself (ids 0..a-1), so the test is not vacuous
+    O0, _ = so.phase1_full_variant(Q, K, V, b, a, so.ANCHOR_FIRST)
+    assert np.abs(O0[0, b:] - O[0, b:]).max() > 1e-3
