@@ -61,7 +61,9 @@ enum {
 enum {
   STAR_ATTN_ANCHOR_FIRST = 0,     /* the method: the first a context tokens (Section 2.1) */
   STAR_ATTN_ANCHOR_PREVIOUS = 1,  /* ablation: the a tokens just before the block (Section 4.1) */
-  STAR_ATTN_ANCHOR_EXTERNAL = 2   /* ablation: anchor K/V handed in separately (Section 4.1) */
+  STAR_ATTN_ANCHOR_EXTERNAL = 2,  /* ablation: anchor K/V handed in separately (Section 4.1) */
+  STAR_ATTN_ANCHOR_PER_BLOCK = 3  /* ablation: a separately given anchor for every block, e.g. the
+                                     first block encoded at position ids that follow the block */
 };
 
 /* Problem shape; sizes in elements / tokens. */
@@ -124,16 +126,20 @@ int star_attn_phase1(const star_attn_shape* shape,
  *   STAR_ATTN_ANCHOR_EXTERNAL  all a rows of K_anchor / V_anchor, then keys
  *                              [i*b, p] of K / V: the anchor's content, or the
  *                              position ids it was encoded with, differ from
- *                              the context's first tokens.
+ *                              the context's first tokens,
+ *   STAR_ATTN_ANCHOR_PER_BLOCK all a rows of slice i of K_anchor / V_anchor, then
+ *                              keys [i*b, p]: one anchor per block (position ids
+ *                              "same as previous block" or sampled per block).
  * a = 0 is "no anchor" in every mode.  The caches receive the context tokens
  * only, exactly as in star_attn_phase1.
  *
- *   K_anchor, V_anchor  in  [B, a, Hkv, d], dtype of the inputs; read only in
- *                 mode EXTERNAL with a > 0 (else may be NULL)
+ *   K_anchor, V_anchor  in  [B, a, Hkv, d] (EXTERNAL) or [B, n, a, Hkv, d] with
+ *                 n = ceil(L / b) (PER_BLOCK; slice 0 is never read), dtype of the
+ *                 inputs; read only in these modes with a > 0 (else may be NULL)
  *   workspace     at least star_attn_phase1_workspace_bytes(shape, mode) bytes,
- *                 256-byte aligned, scratch (only mode EXTERNAL with fp32 tensors
- *                 needs any: a head-major copy of the anchor); unused and may be
- *                 NULL / 0 when that size is 0
+ *                 256-byte aligned, scratch (only separately given anchors in fp32
+ *                 need any: a head-major copy of them); unused and may be NULL / 0
+ *                 when that size is 0
  *   other arguments as in star_attn_phase1
  * Errors as in star_attn_phase1, plus STAR_ATTN_ERR_INVALID_MODE and
  * STAR_ATTN_ERR_WORKSPACE_TOO_SMALL.
@@ -145,7 +151,7 @@ int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode,
                             void* K_cache, void* V_cache,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Workspace bytes star_attn_phase1_anchor needs (0 unless mode EXTERNAL with fp32; 0 for an invalid shape). */
+/* Workspace bytes star_attn_phase1_anchor needs (0 unless anchors are given separately in fp32; 0 for an invalid shape). */
 size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode);
 
 /*

@@ -12,6 +12,7 @@ BF16 = 1
 ANCHOR_FIRST = 0
 ANCHOR_PREVIOUS = 1
 ANCHOR_EXTERNAL = 2
+ANCHOR_PER_BLOCK = 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None

@@ -138,9 +138,12 @@ static int validate_rope(const star_attn_shape* s, double theta, int64_t pos0) {
 }
 
 // Bytes of one head-major copy of the external anchor (K or V), 256-byte padded.
-static size_t anchor_copy_bytes(const star_attn_shape* s) {
+static size_t anchor_copy_bytes(const star_attn_shape* s, int anchor_mode) {
   size_t es = s->dtype == STAR_ATTN_F32 ? 4 : 2;
-  size_t n = (size_t)s->batch * (size_t)s->n_kv_heads * (size_t)s->anchor * (size_t)s->head_dim * es;
+  size_t anchors = anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK
+                       ? (size_t)((s->ctx_len + s->block - 1) / s->block) : 1;
+  size_t n = (size_t)s->batch * (size_t)s->n_kv_heads * anchors * (size_t)s->anchor *
+             (size_t)s->head_dim * es;
   return (n + 255) & ~(size_t)255;
 }
 
@@ -178,8 +181,9 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
 
 size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode) {
   if (validate_shape(shape) != STAR_ATTN_OK) return 0;
-  return anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL && shape->dtype == STAR_ATTN_F32
-             ? 2 * anchor_copy_bytes(shape) : 0;
+  const bool given = anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ||
+                     anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK;
+  return given && shape->dtype == STAR_ATTN_F32 ? 2 * anchor_copy_bytes(shape, anchor_mode) : 0;
 }
 
 }  // extern "C"
@@ -194,13 +198,14 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
   if (rc != STAR_ATTN_OK) return rc;
   if (rope && (rc = validate_rope(shape, rope->theta, rope->pos0)) != STAR_ATTN_OK) return rc;
   if (anchor_mode != STAR_ATTN_ANCHOR_FIRST && anchor_mode != STAR_ATTN_ANCHOR_PREVIOUS &&
-      anchor_mode != STAR_ATTN_ANCHOR_EXTERNAL)
+      anchor_mode != STAR_ATTN_ANCHOR_EXTERNAL && anchor_mode != STAR_ATTN_ANCHOR_PER_BLOCK)
     return STAR_ATTN_ERR_INVALID_MODE;
   if (!Q || !K || !V || !O_ctx || !K_cache || !V_cache) return STAR_ATTN_ERR_NULL_POINTER;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O_ctx) ||
       misaligned(K_cache) || misaligned(V_cache) || ((uintptr_t)LSE_ctx & 3u))
     return STAR_ATTN_ERR_MISALIGNED;
-  const bool ext = anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL && shape->anchor > 0;
+  const bool ext = (anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ||
+                    anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK) && shape->anchor > 0;
   // the fp32 kernel reads a head-major copy of the external anchor (workspace);
   // the bf16 kernel reads the caller's tensors directly
   const bool ext_copy = ext && shape->dtype == STAR_ATTN_F32;
@@ -211,7 +216,8 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
   if (ext_copy) {
     if (!workspace) return STAR_ATTN_ERR_NULL_POINTER;
     if ((uintptr_t)workspace & 255u) return STAR_ATTN_ERR_MISALIGNED;
-    if (workspace_bytes < 2 * anchor_copy_bytes(shape)) return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < 2 * anchor_copy_bytes(shape, anchor_mode))
+      return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
   }
   Geom g = make_geom(shape);
   hipStream_t st = (hipStream_t)hip_stream;
@@ -237,12 +243,14 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
   a.Kin = fused_cache_write ? K : nullptr;
   a.Vin = fused_cache_write ? V : nullptr;
   if (ext_copy) {
-    // the separately given anchor, head-major like the caches: [B, Hkv, a, d]
+    // the separately given anchors, head-major like the caches: [B, Hkv, n_anchor * a, d]
+    // (the [B, n_anchor, a, Hkv, d] input is [B, n_anchor * a, Hkv, d] token-major)
+    const int64_t rows = (anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK ? ceil_div(g.L, g.b) : 1) * g.a;
     Geom ga = g;
-    ga.cap = g.a;
+    ga.cap = rows;
     char* wk = (char*)workspace;
-    char* wv = wk + anchor_copy_bytes(shape);
-    if (launch_cache_write(ga, shape->dtype, K_anchor, V_anchor, wk, wv, g.a, 0, st) != hipSuccess)
+    char* wv = wk + anchor_copy_bytes(shape, anchor_mode);
+    if (launch_cache_write(ga, shape->dtype, K_anchor, V_anchor, wk, wv, rows, 0, st) != hipSuccess)
       return STAR_ATTN_ERR_LAUNCH_FAILED;
     a.Ka = wk; a.Va = wv;
   }

@@ -267,12 +267,18 @@ __device__ __forceinline__ void mask_unit(Scores& x, int key0, int lim, int j4) 
 }
 
 // Mask the score units [key0, key0 + 32) where some row of the wavefront cannot
-// see all of it (wave_lo = smallest causal bound in the wave).
+// see all of it (wave_lo = smallest causal bound in the wave).  Anchor keys are
+// visible to every active row whatever their row numbers in the anchor buffer
+// are: only the range end and inactive rows (row_lim == 0) mask them.
 __device__ __forceinline__ void mask_if_needed(Scores (&s)[RB], int key0, int hi, int wave_lo,
-                                               const int (&row_lim)[RB], int j4) {
+                                               const int (&row_lim)[RB], int j4, bool anchor) {
+  if (anchor) wave_lo = 0x7fffffff;
   if (key0 + 32 > wave_lo || key0 + 32 > hi) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) mask_unit(s[rb], key0, row_lim[rb] < hi ? row_lim[rb] : hi, j4);
+    for (int rb = 0; rb < RB; ++rb) {
+      int lim = anchor ? (row_lim[rb] > 0 ? hi : 0) : (row_lim[rb] < hi ? row_lim[rb] : hi);
+      mask_unit(s[rb], key0, lim, j4);
+    }
   }
 }
 
@@ -425,10 +431,10 @@ __device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, cons
     stage<SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB, r.pA,
                                                                        c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    mask_if_needed(r.sA, nk0, nhi, wave_lo, row_lim, la.j4);
+    mask_if_needed(r.sA, nk0, nhi, wave_lo, row_lim, la.j4, t + 1 < seq.n_a);
     stage<SAFE, true, true, true, KN + H, VC + H, true>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    mask_if_needed(r.sB, nk0 + 32, nhi, wave_lo, row_lim, la.j4);
+    mask_if_needed(r.sB, nk0 + 32, nhi, wave_lo, row_lim, la.j4, t + 1 < seq.n_a);
   } else {
     stage<SAFE, false, true, true, 0, VC>(w, la, r.sA, r.sB, r.pB, r.pA, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
@@ -466,9 +472,9 @@ __device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const
   }
   __builtin_amdgcn_s_barrier();
   stage<SAFE, true, false, false, K0, 0>(w, la, r.sA, r.sA, r.pA, r.pA, c, alpha, pre);
-  mask_if_needed(r.sA, key0, hi, wave_lo, row_lim, la.j4);
+  mask_if_needed(r.sA, key0, hi, wave_lo, row_lim, la.j4, seq.n_a > 0);
   stage<SAFE, true, false, false, K0 + H, 0>(w, la, r.sB, r.sA, r.pA, r.pA, c, alpha, pre);
-  mask_if_needed(r.sB, key0 + 32, hi, wave_lo, row_lim, la.j4);
+  mask_if_needed(r.sB, key0 + 32, hi, wave_lo, row_lim, la.j4, seq.n_a > 0);
   // first unit: its row maximum becomes the reference (nothing to rescale yet)
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
@@ -636,8 +642,10 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1
   const bool ext = anchor_range(g, a.anchor_mode, i, &a_lo, &a_hi);
   seq.a_lo = (int)a_lo;
   seq.a_hi = (int)a_hi;
-  seq.Ka = ext ? (const char*)a.Ka + ((size_t)beta * g.a * g.Hkv + kvh) * ROWB : Kb;
-  seq.Va = ext ? (const char*)a.Va + ((size_t)beta * g.a * g.Hkv + kvh) * ROWB : Vb;
+  // external anchors: token-major, n_anchor * a rows per batch
+  const size_t anchor_rows = (size_t)(a.anchor_mode == ANCHOR_PER_BLOCK ? n : 1) * g.a;
+  seq.Ka = ext ? (const char*)a.Ka + ((size_t)beta * anchor_rows * g.Hkv + kvh) * ROWB : Kb;
+  seq.Va = ext ? (const char*)a.Va + ((size_t)beta * anchor_rows * g.Hkv + kvh) * ROWB : Vb;
   seq.Kl = Kb;
   seq.Vl = Vb;
   seq.l_stride = kv_stride;

@@ -152,9 +152,11 @@ __global__ __launch_bounds__(ROWS) void phase1_f32_kernel(Phase1Args a, int tile
   int64_t last = row0 + ROWS < e ? row0 + ROWS : e;   // exclusive bound of the tile's rows
   int64_t a_lo, a_hi;                                              // anchor: fully visible
   if (anchor_range(g, a.anchor_mode, i, &a_lo, &a_hi)) {
-    const float* Kab = (const float*)a.Ka + ((int64_t)beta * g.Hkv + kvh) * g.a * D;
-    const float* Vab = (const float*)a.Va + ((int64_t)beta * g.Hkv + kvh) * g.a * D;
-    attend_range<D>(st, Kab, Vab, a_lo, a_hi, limit, Ks, Vs);
+    const int64_t anchor_rows = (a.anchor_mode == ANCHOR_PER_BLOCK ? (g.L + g.b - 1) / g.b : 1) * g.a;
+    const float* Kab = (const float*)a.Ka + ((int64_t)beta * g.Hkv + kvh) * anchor_rows * D;
+    const float* Vab = (const float*)a.Va + ((int64_t)beta * g.Hkv + kvh) * anchor_rows * D;
+    // rows of the anchor buffer are not positions: every one is visible
+    attend_range<D>(st, Kab, Vab, a_lo, a_hi, active ? a_hi : 0, Ks, Vs);
   } else {
     attend_range<D>(st, Kb, Vb, a_lo, a_hi, limit, Ks, Vs);
   }

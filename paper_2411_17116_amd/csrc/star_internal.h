@@ -40,7 +40,7 @@ struct Geom {
 
 // What prefixes a context block after the first (values of the public
 // STAR_ATTN_ANCHOR_* constants).
-enum AnchorMode { ANCHOR_FIRST = 0, ANCHOR_PREVIOUS = 1, ANCHOR_EXTERNAL = 2 };
+enum AnchorMode { ANCHOR_FIRST = 0, ANCHOR_PREVIOUS = 1, ANCHOR_EXTERNAL = 2, ANCHOR_PER_BLOCK = 3 };
 
 struct Phase1Args {
   Geom g;
@@ -50,18 +50,21 @@ struct Phase1Args {
   const void* Kc;       // caches [B, Hkv, cap, d], already holding the context
   const void* Vc;
   int32_t anchor_mode;  // AnchorMode
-  const void* Ka;       // ANCHOR_EXTERNAL: anchor keys / values; head-major [B, Hkv, a, d]
-  const void* Va;       // for the fp32 kernel, token-major [B, a, Hkv, d] for the bf16 one
+  const void* Ka;       // ANCHOR_EXTERNAL / PER_BLOCK: anchor keys / values of n_anchor =
+  const void* Va;       // 1 / n anchors; head-major [B, Hkv, n_anchor * a, d] for the fp32
+                        // kernel, token-major [B, n_anchor, a, Hkv, d] for the bf16 one
   const void* Kin;      // bf16 kernel: the token-major inputs [B, L, Hkv, d] to read keys /
   const void* Vin;      // values from (and to file in the caches); null: read the caches
 };
 
 // Anchor key rows [*lo, *hi) of 0-based block i, and whether they index the
-// external anchor buffers (true) or the caches (false).  Block 0 has none.
+// external anchor buffers (true; rows counted over all of a batch's anchors) or
+// the context keys (false).  Block 0 has none.
 __host__ __device__ inline bool anchor_range(const Geom& g, int mode, int64_t i, int64_t* lo,
                                              int64_t* hi) {
   if (i == 0 || g.a == 0) { *lo = 0; *hi = 0; return false; }
   if (mode == ANCHOR_PREVIOUS) { *lo = i * g.b - g.a; *hi = i * g.b; return false; }
+  if (mode == ANCHOR_PER_BLOCK) { *lo = i * g.a; *hi = (i + 1) * g.a; return true; }
   *lo = 0; *hi = g.a;
   return mode == ANCHOR_EXTERNAL;
 }

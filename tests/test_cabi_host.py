@@ -164,7 +164,7 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
 def test_phase1_anchor_variant_arguments(lib):
     shape = good_shape()
     EXT = binding.ANCHOR_EXTERNAL
-    for mode in (-1, 3, 99):
+    for mode in (-1, 4, 99):
         assert _p1a(lib, shape, mode) == ERR["INVALID_MODE"]
     assert _p1a(lib, good_shape(anchor=300), binding.ANCHOR_PREVIOUS) == ERR["ANCHOR_GT_BLOCK"]
     for mode in (binding.ANCHOR_FIRST, binding.ANCHOR_PREVIOUS, EXT):
@@ -182,6 +182,11 @@ def test_phase1_anchor_variant_arguments(lib):
     assert sa.binding.phase1_workspace_bytes(f32, binding.ANCHOR_FIRST) == 0
     assert sa.binding.phase1_workspace_bytes(f32, binding.ANCHOR_PREVIOUS) == 0
     assert sa.binding.phase1_workspace_bytes(good_shape(batch=0), EXT) == 0
+    # one anchor per block: n = 4 of them
+    assert sa.binding.phase1_workspace_bytes(f32, binding.ANCHOR_PER_BLOCK) == 4 * need
+    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_PER_BLOCK) == 0
+    assert _p1a(lib, shape, binding.ANCHOR_PER_BLOCK, Ka=None) == ERR["NULL_POINTER"]
+    assert _p1a(lib, f32, binding.ANCHOR_PER_BLOCK, ws_bytes=need) == ERR["WORKSPACE_TOO_SMALL"]
     assert _p1a(lib, f32, EXT, Ka=None, ws_bytes=need) == ERR["NULL_POINTER"]
     assert _p1a(lib, f32, EXT, ws=None, ws_bytes=need) == ERR["NULL_POINTER"]
     assert _p1a(lib, f32, EXT, ws=0x1010, ws_bytes=need) == ERR["MISALIGNED"]

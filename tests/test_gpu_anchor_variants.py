@@ -17,10 +17,12 @@ def _run_variant(cfg, mode, triples=None, seed=5):
     run = ph.HipRun(cfg, inp, "cuda")
     dt = inp.K.dtype
     Ka = Va = ws = None
-    if mode == sa.ANCHOR_EXTERNAL:
+    if mode in (sa.ANCHOR_EXTERNAL, sa.ANCHOR_PER_BLOCK):
         gen = torch.Generator(device="cpu").manual_seed(seed)
-        Ka = torch.randn((cfg.B, cfg.a, cfg.Hkv, cfg.d), generator=gen).to(dt).cuda()
-        Va = torch.randn((cfg.B, cfg.a, cfg.Hkv, cfg.d), generator=gen).to(dt).cuda()
+        dims = (cfg.B, cfg.a, cfg.Hkv, cfg.d) if mode == sa.ANCHOR_EXTERNAL else \
+            (cfg.B, cfg.n_blocks, cfg.a, cfg.Hkv, cfg.d)
+        Ka = torch.randn(dims, generator=gen).to(dt).cuda()
+        Va = torch.randn(dims, generator=gen).to(dt).cuda()
         n = sa.phase1_workspace_bytes(run.shape, mode)
         ws = torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
     print(f"[{cfg.name}] mode={mode} L={cfg.L} b={cfg.b} a={cfg.a} Hq={cfg.Hq} Hkv={cfg.Hkv}", flush=True)
@@ -52,7 +54,7 @@ def _run_variant(cfg, mode, triples=None, seed=5):
     return run, inp
 
 
-MODES = [sa.ANCHOR_PREVIOUS, sa.ANCHOR_EXTERNAL]
+MODES = [sa.ANCHOR_PREVIOUS, sa.ANCHOR_EXTERNAL, sa.ANCHOR_PER_BLOCK]
 
 
 @pytest.mark.parametrize("mode", MODES)
@@ -109,3 +111,54 @@ def test_config3_shape_anchor_variants_sampled(mode):
     triples = workloads.phase1_sample(cfg, inp.planted_ctx, n_random=96)
     del inp
     _run_variant(cfg, mode, triples=triples)
+
+
+def test_position_id_ablation_end_to_end():
+    """Section 4.1, "position IDs same as previous block", on the GPU path: the
+    projections arrive unrotated; star_attn_rope rotates Q and K at their own
+    positions and builds, for every block, the first block's keys rotated at the
+    positions just before that block; star_attn_phase1_anchor (PER_BLOCK) then
+    attends.  The oracle composes the same steps in fp64 (with the storage
+    rounding of the rotated tensors)."""
+    from tests.test_gpu_rope import _stored
+    theta = 500000.0
+    cfg = workloads.StarConfig("posids", "bf16", 1, 8, 2, 128, 2048, 512, 512, 4, 1, seed=41,
+                               n_planted=4)
+    inp = workloads.make_inputs(cfg, "cuda")
+    run = ph.HipRun(cfg, inp, "cuda")
+    stored = _stored(cfg.dtype)
+    n, a, b = cfg.n_blocks, cfg.a, cfg.b
+    Qp, Kp = inp.Q.clone(), inp.K.clone()
+    sa.rope(run.shape, inp.Q, inp.Q, theta)
+    sa.rope(run.shape, inp.K, inp.K, theta)
+    Ka = torch.zeros((cfg.B, n, a, cfg.Hkv, cfg.d), dtype=inp.K.dtype, device="cuda")
+    Va = torch.zeros_like(Ka)
+    first = Kp[:, :a].contiguous()
+    ashape = sa.StarShape.make(cfg.dtype, cfg.B, cfg.Hq, cfg.Hkv, cfg.d, a, a, a, a)
+    for i in range(1, n):
+        out = torch.empty_like(first)
+        sa.rope(ashape, first, out, theta, pos0=i * b - a)
+        Ka[:, i] = out
+        Va[:, i] = inp.V[:, :a]
+    sa.phase1_anchor(run.shape, sa.ANCHOR_PER_BLOCK, inp.Q, inp.K, inp.V, run.O_ctx, run.Kc, run.Vc,
+                     K_anchor=Ka, V_anchor=Va, LSE_ctx=run.LSE_ctx)
+    torch.cuda.synchronize()
+    # oracle: same composition
+    Qp64, Kp64 = Qp.float().cpu().numpy(), Kp.float().cpu().numpy()
+    V64 = inp.V.float().cpu().numpy()
+    pos = np.arange(cfg.L)
+    Qr = stored(so.rope_rotate(Qp64, pos, theta))
+    Kr = stored(so.rope_rotate(Kp64, pos, theta))
+    Ka_o = np.zeros((cfg.B, n, a, cfg.Hkv, cfg.d))
+    Va_o = np.zeros_like(Ka_o)
+    for i in range(1, n):
+        Ka_o[:, i] = stored(so.rope_rotate(Kp64[:, :a], i * b - a + np.arange(a), theta))
+        Va_o[:, i] = V64[:, :a]
+    triples = [(0, h, p) for h in (0, 3, 7) for p in list(range(0, cfg.L, 37)) + [b - 1, b, b + 1, cfg.L - 1]]
+    eo = el = 0.0
+    for beta, h, p in triples:
+        o, l = so.phase1_row_variant(Qr, Kr, V64, beta, h, p, b, a, so.ANCHOR_PER_BLOCK, Ka_o, Va_o)
+        eo = max(eo, float(np.abs(run.O_ctx[beta, p, h].float().cpu().numpy() - o).max()))
+        el = max(el, abs(float(run.LSE_ctx[beta, h, p]) - l))
+    print(f"   position-id ablation: max|dO|={eo:.3g} max|dLSE|={el:.3g}", flush=True)
+    assert eo <= ph.TOL["bf16"]["o"] and el <= ph.TOL["bf16"]["lse"]
