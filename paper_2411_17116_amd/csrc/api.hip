@@ -41,10 +41,6 @@ static Geom make_geom(const star_attn_shape* s) {
 static int64_t ceil_div(int64_t x, int64_t y) { return (x + y - 1) / y; }
 static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
 
-// Row tiling of the bf16 row-tiled kernels (defined with them).
-int flash_heads_per_workgroup(int G);
-int flash_tokens_per_workgroup(int G);
-
 // Workgroups of the decode kernel that are resident at once on an MI355X:
 // 256 CUs x 2 (the kernel's 64 KiB LDS ring allows two per CU).
 #ifndef STAR_DECODE_WGS_PER_CU

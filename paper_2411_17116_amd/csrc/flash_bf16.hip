@@ -41,9 +41,6 @@
 
 namespace star {
 
-int flash_heads_per_workgroup(int G);
-int flash_tokens_per_workgroup(int G);
-
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;

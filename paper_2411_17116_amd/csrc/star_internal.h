@@ -115,6 +115,11 @@ __host__ __device__ inline void split_range(const SplitPlan& p, int64_t L, int64
   }
 }
 
+// Row tiling of the bf16 row-tiled kernels: heads of one KV group that share a
+// workgroup, and tokens per workgroup (the split plan sizes its grids with them).
+int flash_heads_per_workgroup(int G);
+int flash_tokens_per_workgroup(int G);
+
 // Host-side launchers (each returns the hipError_t of its launch).
 // K and / or V (a null source is skipped) into rows [dst_row, dst_row + n_tokens).
 hipError_t launch_cache_write(const Geom& g, int dtype, const void* K, const void* V,
