@@ -225,3 +225,41 @@ def test_rope_entry_point_arguments(lib):
     assert rot(tokens=0) == ERR["INVALID_SHAPE"]
     assert rot(X=None) == ERR["NULL_POINTER"]
     assert rot(Y=0x1002) == ERR["MISALIGNED"]
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, and a
+    C caller must link against the library by the declared names."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "star_attn.h"\n'
+        "int main(void) {\n"
+        "  star_attn_shape s = {0};\n"
+        "  s.dtype = STAR_ATTN_BF16; s.batch = 0;\n"
+        "  /* every call below is rejected by validation: nothing is enqueued */\n"
+        "  int rc = star_attn_phase1(&s, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
+        "  rc |= star_attn_phase2(&s, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
+        "  rc |= star_attn_phase1_anchor(&s, STAR_ATTN_ANCHOR_PER_BLOCK, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
+        "  rc |= star_attn_phase1_rope(&s, 10000.0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
+        "  rc |= star_attn_phase2_rope(&s, 10000.0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
+        "  rc |= star_attn_rope(&s, 1, 1, 0, 10000.0, 0, 0, 0);\n"
+        "  return (rc != 0 && star_attn_workspace_bytes(&s, 1) == 0 &&\n"
+        "          star_attn_phase1_workspace_bytes(&s, 0) == 0 &&\n"
+        "          star_attn_status_string(rc) != 0 && star_attn_kernel_path(&s) == 0) ? 0 : 1;\n"
+        "}\n")
+    inc = os.path.join(ROOT, "include")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", f"-I{inc}", str(src)],
+                   check=True)
+    if not os.path.exists(sa.lib_path()):
+        pytest.skip("library not built")
+    exe = tmp_path / "use_header"
+    libdir = os.path.dirname(sa.lib_path())
+    r = subprocess.run([gcc, "-std=c99", f"-I{inc}", str(src), "-o", str(exe), f"-L{libdir}", "-lstarattn",
+                        f"-Wl,-rpath,{libdir}"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    assert subprocess.run([str(exe)]).returncode == 0
