@@ -5,13 +5,17 @@
 //
 // Shape of the computation
 //   * A workgroup is 8 wavefronts (two per SIMD, one workgroup per CU); each
-//     wavefront owns 32 query rows (two blocks of 16) and the whole head dimension.  The rows of a
-//     workgroup are GQA-packed: up to 8 query heads of one KV group times 32 to
-//     256 tokens, so the K/V tiles a workgroup streams are fetched from L2 once
-//     per 256 rows, and the wavefronts' causal frontiers lie within those tokens.
+//     wavefront owns 32 query rows (two blocks of 16) and the whole head
+//     dimension.  The rows of a workgroup are GQA-packed: up to 8 query heads of
+//     one KV group times 32 to 256 tokens, so the K/V tiles a workgroup streams
+//     are fetched from L2 once per 256 rows, and the wavefronts' causal
+//     frontiers lie within those tokens.
 //   * K/V tiles of 64 keys are DMA'd from HBM/L2 straight into LDS
 //     (global_load_lds_dwordx4, no VGPR staging), double-buffered, one barrier
-//     per tile.  Inside a 256-byte key row the sixteen 16-byte chunks are
+//     per tile.  Key rows may sit anywhere a fixed stride apart: phase 1 reads
+//     the caller's token-major K/V in place (and files them in the head-major
+//     caches when it is done), phase 2 reads the caches.  In LDS, inside a
+//     256-byte key row the sixteen 16-byte chunks are
 //     XOR-swizzled so that both the K operand reads (ds_read_b128) and the
 //     transposing V operand reads (ds_read_b64_tr_b16) are bank-conflict free
 //     without padding.
