@@ -147,11 +147,27 @@ def cpu_baseline(cfg, inp, budget_s=12.0):
     dt = time.time() - t0
     rows_per_s = done / dt
     tok_per_s = rows_per_s / cfg.Hq
-    return {
+    out = {
         "value": tok_per_s, "unit": "tok/s", "cores": cores, "kind": "oracle",
         "sample": f"phase 1, {done} seeded (batch, head, row) triples of {cfg.name} in {dt:.1f} s; "
                   f"{rows_per_s:.1f} rows/s divided by Hq={cfg.Hq} (extrapolated to whole tokens)",
     }
+    if cfg.nd:
+        # one decode step = Hq * B rows of global attention over the whole cache: time a
+        # few (batch, head) rows of the first decode step (context + query tokens cached)
+        from tests.parity_harness import CacheView
+        Kc = CacheView(inp.K.cpu(), inp.Kq.cpu(), inp.Kd[:, :1].cpu())
+        Vc = CacheView(inp.V.cpu(), inp.Vq.cpu(), inp.Vd[:, :1].cpu())
+        heads = sorted({0, cfg.Hq // 2, cfg.Hq - 1})
+        t0 = time.time()
+        so.phase2_rows(LazyTensor(inp.Qd[:, :1].cpu()), Kc, Vc, cfg.L, cfg.b, cfg.L + cfg.lq,
+                       heads=heads, rows=[0])
+        dt2 = time.time() - t0
+        out["decode_s_per_step"] = dt2 / len(heads) * cfg.Hq
+        out["decode_sample"] = (f"phase 2, first decode step, {len(heads)} of {cfg.Hq} heads x {cfg.B} batch "
+                                f"in {dt2:.2f} s on one core (per-part and global attention), "
+                                f"extrapolated to all heads")
+    return out
 
 
 _POLLER = r"""
