@@ -17,6 +17,8 @@ resident in HBM before the timed region.  Prints ONE JSON line:
   full_causal         the same kernels run with block = anchor = L (one block)
   cpu_baseline        the fp64 oracle timed on this host's cores on a bounded
                       sample of the same workload (a reported baseline only)
+  anchor_variants     phase 1 under the ablation study's anchor variants, ms per call
+  rope                the entry points that take unrotated projections
   power               socket power and shader clock that `amd-smi` reports while
                       phase 1 runs back to back for about two seconds (the MFMA
                       peak assumes 2.4 GHz; under this load the chip runs at its
@@ -328,6 +330,34 @@ def rope_cost(cfg, shape, inp, bufs, theta=500000.0):
             "note": "star_attn_rope on Q in place (bytes = Q read + written), and star_attn_phase1_rope"}
 
 
+def anchor_variants(cfg, shape, inp, bufs):
+    """Phase 1 under the ablation study's anchor variants (same flops as the
+    method when the anchor has `a` tokens): milliseconds per call."""
+    n = cfg.n_blocks
+    Ka1 = inp.K[:, :cfg.a].contiguous()
+    Va1 = inp.V[:, :cfg.a].contiguous()
+    KaN = Ka1[:, None].expand(cfg.B, n, cfg.a, cfg.Hkv, cfg.d).contiguous()
+    VaN = Va1[:, None].expand(cfg.B, n, cfg.a, cfg.Hkv, cfg.d).contiguous()
+    modes = {"previous_block": (sa.ANCHOR_PREVIOUS, None, None),
+             "external": (sa.ANCHOR_EXTERNAL, Ka1, Va1),
+             "per_block": (sa.ANCHOR_PER_BLOCK, KaN, VaN)}
+    out = {}
+    flops = phase1_flops(cfg)
+    for name, (mode, Ka, Va) in modes.items():
+        t = Timer()
+        idx = []
+        for _ in range(3):
+            e = t.start()
+            sa.phase1_anchor(shape, mode, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"],
+                             K_anchor=Ka, V_anchor=Va)
+            idx.append(t.stop(e))
+        torch.cuda.synchronize()
+        ms = min(t.ms(i) for i in idx[1:])
+        out[name] = {"ms": ms, "tflops": flops / (ms * 1e-3) / 1e12}
+    out["note"] = "star_attn_phase1_anchor; every variant attends a keys of anchor + the causal block, as the method does"
+    return out
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summaries
     (profiles/traffic.json), or None if that kernel/workload was not profiled."""
@@ -349,6 +379,8 @@ def main():
     ap.add_argument("--no-full-causal", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph replay of the decode loop")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip timing the anchor variants of the ablation study")
     ap.add_argument("--no-rope", action="store_true",
                     help="skip timing the entry points that take unrotated projections")
     ap.add_argument("--no-power", action="store_true",
@@ -467,6 +499,8 @@ def main():
                               "flop_ratio_vs_star": f_flops / flops}
     if "decode" in sections and cfg.nd and not args.no_graph:
         out["phase2"]["decode_graph"] = decode_graph(cfg, shape, bufs)
+    if "phase1" in sections and not args.no_variants and cfg.dtype == "bf16" and cfg.name != "C4":
+        out["anchor_variants"] = anchor_variants(cfg, shape, inp, bufs)
     if "phase1" in sections and not args.no_rope:
         out["rope"] = rope_cost(cfg, shape, inp, bufs)
         # the caches now hold rotated keys; nothing below reads them
