@@ -8,8 +8,10 @@
  * K/V is kept.  Phase 2 (Section 2.2, Eq. 1-4, Algorithm 2) lets query and
  * generated tokens attend to the whole cache: each cached part yields a local
  * attention output and the log of its softmax denominator, and the parts are
- * merged by rescaling with those log-sum-exp statistics.  The paper's context
- * hosts are context blocks resident on the one GPU.
+ * merged by rescaling with those log-sum-exp statistics.  star_attn_phase1 and
+ * star_attn_phase2 treat the paper's context hosts as context blocks resident
+ * on the one GPU; STAR_ATTN_ANCHOR_ALL_BLOCKS, star_attn_phase2_partial and
+ * star_attn_merge are one host's share when the context is spread over several.
  *
  * Conventions
  *   - Every pointer is DEVICE memory owned by the caller unless it says "host".
@@ -62,8 +64,11 @@ enum {
   STAR_ATTN_ANCHOR_FIRST = 0,     /* the method: the first a context tokens (Section 2.1) */
   STAR_ATTN_ANCHOR_PREVIOUS = 1,  /* ablation: the a tokens just before the block (Section 4.1) */
   STAR_ATTN_ANCHOR_EXTERNAL = 2,  /* ablation: anchor K/V handed in separately (Section 4.1) */
-  STAR_ATTN_ANCHOR_PER_BLOCK = 3  /* ablation: a separately given anchor for every block, e.g. the
+  STAR_ATTN_ANCHOR_PER_BLOCK = 3, /* ablation: a separately given anchor for every block, e.g. the
                                      first block encoded at position ids that follow the block */
+  STAR_ATTN_ANCHOR_ALL_BLOCKS = 4 /* a context host's share (Algorithm 1): the call's context is a
+                                     run of blocks that starts after the global first block, and
+                                     the anchor handed in prefixes every one of them */
 };
 
 /* Problem shape; sizes in elements / tokens. */
@@ -130,10 +135,17 @@ int star_attn_phase1(const star_attn_shape* shape,
  *   STAR_ATTN_ANCHOR_PER_BLOCK all a rows of slice i of K_anchor / V_anchor, then
  *                              keys [i*b, p]: one anchor per block (position ids
  *                              "same as previous block" or sampled per block).
+ *   STAR_ATTN_ANCHOR_ALL_BLOCKS  as EXTERNAL, and block 0 of the call is prefixed
+ *                              as well: Algorithm 1 as it runs on a host that owns
+ *                              blocks i0 .. i1-1 (i0 >= 1) of a longer context.  The
+ *                              host passes its own tokens as Q / K / V (L = their
+ *                              number), the first a tokens' K / V of the whole
+ *                              context as the anchor, and keeps only its own
+ *                              tokens' K / V, in its own caches.
  * a = 0 is "no anchor" in every mode.  The caches receive the context tokens
  * only, exactly as in star_attn_phase1.
  *
- *   K_anchor, V_anchor  in  [B, a, Hkv, d] (EXTERNAL) or [B, n, a, Hkv, d] with
+ *   K_anchor, V_anchor  in  [B, a, Hkv, d] (EXTERNAL, ALL_BLOCKS) or [B, n, a, Hkv, d] with
  *                 n = ceil(L / b) (PER_BLOCK; slice 0 is never read), dtype of the
  *                 inputs; read only in these modes with a > 0 (else may be NULL)
  *   workspace     at least star_attn_phase1_workspace_bytes(shape, mode) bytes,
@@ -185,6 +197,50 @@ int star_attn_phase2(const star_attn_shape* shape,
                      float* O_part, float* LSE_part,
                      void* O,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Phase 2 on one host of several (Section 2.2; Algorithm 2).
+ *
+ * When the cache is spread over hosts, the new tokens' queries go to every
+ * host, each host returns the pair (A_h, log s_h) of Eq. 1-2 for its own cache,
+ * and the query host combines the gathered pairs with Eq. 3-4.
+ * star_attn_phase2_partial is one host's share of such a call and
+ * star_attn_merge is the query host's aggregation; moving the pairs between
+ * devices is the caller's business.  `shape` describes the HOST's share:
+ * ctx_len = the context tokens its caches hold, cache_capacity = its caches' rows.
+ *
+ * star_attn_phase2_partial
+ *   Kq, Vq     both NULL: a context host.  Nothing is appended and every new
+ *              token attends to cache rows [0, cache_len), all visible.
+ *              both given: the query host.  As in star_attn_phase2 they are
+ *              appended at rows [cache_len, cache_len + q_len) and new token j
+ *              attends to rows [0, cache_len + j].
+ *   A          out  [B, Hq, q_len, d] fp32: local attention output (Eq. 1)
+ *   LSE        out  [B, Hq, q_len] fp32: natural log of the softmax denominator
+ *              of the scaled logits (log of Eq. 2)
+ *   other arguments, workspace and errors as in star_attn_phase2
+ *
+ * star_attn_merge  (B, Hq, d and the dtype of O come from `shape`; its other
+ *                   fields must be valid but are not used)
+ *   n_parts    number of gathered pairs, >= 1
+ *   A_parts    in   [n_parts, B, Hq, q_len, d] fp32 (one contiguous slab per host)
+ *   LSE_parts  in   [n_parts, B, Hq, q_len] fp32; -inf marks a host that saw no
+ *              key: its slab is not read and it contributes nothing
+ *   O          out  [B, q_len, Hq, d] in the storage dtype; may be NULL if A is given
+ *   A, LSE     out  the merged pair in fp32, layouts as above (for merging in
+ *              stages); each may be NULL
+ * Needs no workspace.  Pairs are folded in index order: deterministic.
+ */
+int star_attn_phase2_partial(const star_attn_shape* shape,
+                             int64_t cache_len, int64_t q_len,
+                             const void* Qq, const void* Kq, const void* Vq,
+                             void* K_cache, void* V_cache,
+                             float* A, float* LSE,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+int star_attn_merge(const star_attn_shape* shape, int64_t n_parts, int64_t q_len,
+                    const float* A_parts, const float* LSE_parts,
+                    void* O, float* A, float* LSE, void* hip_stream);
 
 /*
  * Unrotated projections: rotary position embedding applied inside the calls.

@@ -13,6 +13,7 @@ ANCHOR_FIRST = 0
 ANCHOR_PREVIOUS = 1
 ANCHOR_EXTERNAL = 2
 ANCHOR_PER_BLOCK = 3
+ANCHOR_ALL_BLOCKS = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -82,6 +83,10 @@ def load_library():
     lib.star_attn_rope.argtypes = [P, ctypes.c_int32, i64, i64, dbl, vp, vp, vp]
     lib.star_attn_phase2.restype = ctypes.c_int
     lib.star_attn_phase2.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.star_attn_phase2_partial.restype = ctypes.c_int
+    lib.star_attn_phase2_partial.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.star_attn_merge.restype = ctypes.c_int
+    lib.star_attn_merge.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp]
     lib.star_attn_status_string.restype = ctypes.c_char_p
     lib.star_attn_status_string.argtypes = [ctypes.c_int]
     lib.star_attn_kernel_path.restype = ctypes.c_char_p
@@ -200,4 +205,25 @@ def phase2(shape: StarShape, cache_len: int, Qq, Kq, Vq, K_cache, V_cache, O, wo
         ctypes.byref(shape), int(cache_len), int(q_len), _ptr(Qq), _ptr(Kq), _ptr(Vq),
         _ptr(K_cache), _ptr(V_cache), _ptr(O_part), _ptr(LSE_part), _ptr(O),
         _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)
+
+
+def phase2_partial(shape: StarShape, cache_len: int, Qq, K_cache, V_cache, A, LSE, workspace,
+                   Kq=None, Vq=None, stream=None) -> None:
+    """star_attn_phase2_partial: one host's pair (A, LSE) for the q_len = Qq.shape[1]
+    new tokens; with Kq/Vq the query host's share (append, then attend causally)."""
+    q_len = Qq.shape[1]
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load_library().star_attn_phase2_partial(
+        ctypes.byref(shape), int(cache_len), int(q_len), _ptr(Qq), _ptr(Kq), _ptr(Vq),
+        _ptr(K_cache), _ptr(V_cache), _ptr(A), _ptr(LSE), _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)
+
+
+def merge(shape: StarShape, A_parts, LSE_parts, O=None, A=None, LSE=None, stream=None) -> None:
+    """star_attn_merge: Eq. 3-4 over the n_parts = A_parts.shape[0] gathered pairs."""
+    n_parts, q_len = A_parts.shape[0], A_parts.shape[3]
+    rc = load_library().star_attn_merge(
+        ctypes.byref(shape), int(n_parts), int(q_len), _ptr(A_parts), _ptr(LSE_parts), _ptr(O),
+        _ptr(A), _ptr(LSE), _stream(stream))
     _check(rc)

@@ -178,7 +178,8 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
 size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode) {
   if (validate_shape(shape) != STAR_ATTN_OK) return 0;
   const bool given = anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ||
-                     anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK;
+                     anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK ||
+                     anchor_mode == STAR_ATTN_ANCHOR_ALL_BLOCKS;
   return given && shape->dtype == STAR_ATTN_F32 ? 2 * anchor_copy_bytes(shape, anchor_mode) : 0;
 }
 
@@ -194,14 +195,16 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
   if (rc != STAR_ATTN_OK) return rc;
   if (rope && (rc = validate_rope(shape, rope->theta, rope->pos0)) != STAR_ATTN_OK) return rc;
   if (anchor_mode != STAR_ATTN_ANCHOR_FIRST && anchor_mode != STAR_ATTN_ANCHOR_PREVIOUS &&
-      anchor_mode != STAR_ATTN_ANCHOR_EXTERNAL && anchor_mode != STAR_ATTN_ANCHOR_PER_BLOCK)
+      anchor_mode != STAR_ATTN_ANCHOR_EXTERNAL && anchor_mode != STAR_ATTN_ANCHOR_PER_BLOCK &&
+      anchor_mode != STAR_ATTN_ANCHOR_ALL_BLOCKS)
     return STAR_ATTN_ERR_INVALID_MODE;
   if (!Q || !K || !V || !O_ctx || !K_cache || !V_cache) return STAR_ATTN_ERR_NULL_POINTER;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O_ctx) ||
       misaligned(K_cache) || misaligned(V_cache) || ((uintptr_t)LSE_ctx & 3u))
     return STAR_ATTN_ERR_MISALIGNED;
   const bool ext = (anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ||
-                    anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK) && shape->anchor > 0;
+                    anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK ||
+                    anchor_mode == STAR_ATTN_ANCHOR_ALL_BLOCKS) && shape->anchor > 0;
   // the fp32 kernel reads a head-major copy of the external anchor (workspace);
   // the bf16 kernel reads the caller's tensors directly
   const bool ext_copy = ext && shape->dtype == STAR_ATTN_F32;
@@ -298,25 +301,32 @@ int star_attn_rope(const star_attn_shape* shape, int32_t n_heads, int64_t n_toke
 
 }  // extern "C"
 
-// Phase 2 behind both public variants.  With `rope`, Qq is rotated in place and
+// Phase 2 behind every public variant.  With `rope`, Qq is rotated in place and
 // Kq on its way into the cache (new token j sits at pos0 + cache_len + j).
+// `pair` (a host's share of a call): the result is left as the fp32 pair
+// (A, LSE) instead of O, and Kq == Vq == NULL means "append nothing, every new
+// token sees cache rows [0, cache_len)".
 static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t cache_len,
                        int64_t q_len, void* Qq, const void* Kq, const void* Vq, void* K_cache,
-                       void* V_cache, float* O_part, float* LSE_part, void* O, void* workspace,
-                       size_t workspace_bytes, void* hip_stream) {
+                       void* V_cache, float* O_part, float* LSE_part, void* O, bool pair, float* A,
+                       float* LSE, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = validate_shape(shape);
   if (rc != STAR_ATTN_OK) return rc;
   if (rope && (rc = validate_rope(shape, rope->theta, rope->pos0)) != STAR_ATTN_OK) return rc;
   if (q_len <= 0 || q_len > (1 << 20) || cache_len < shape->ctx_len) return STAR_ATTN_ERR_INVALID_SHAPE;
-  if (cache_len + q_len > shape->cache_capacity) return STAR_ATTN_ERR_CACHE_OVERFLOW;
-  if (!Qq || !Kq || !Vq || !K_cache || !V_cache || !O || !workspace) return STAR_ATTN_ERR_NULL_POINTER;
+  const bool append = !(pair && !Kq && !Vq);
+  const int64_t total = cache_len + (append ? q_len : 0);
+  if (total > shape->cache_capacity) return STAR_ATTN_ERR_CACHE_OVERFLOW;
+  if (!Qq || !K_cache || !V_cache || !workspace) return STAR_ATTN_ERR_NULL_POINTER;
+  if (append && (!Kq || !Vq)) return STAR_ATTN_ERR_NULL_POINTER;
+  if (pair ? (!A || !LSE) : !O) return STAR_ATTN_ERR_NULL_POINTER;
   if ((O_part == nullptr) != (LSE_part == nullptr)) return STAR_ATTN_ERR_NULL_POINTER;
   if (misaligned(Qq) || misaligned(Kq) || misaligned(Vq) || misaligned(K_cache) ||
       misaligned(V_cache) || misaligned(O) || misaligned(O_part) || ((uintptr_t)LSE_part & 3u) ||
-      ((uintptr_t)workspace & 255u))
+      misaligned(A) || ((uintptr_t)LSE & 3u) || ((uintptr_t)workspace & 255u))
     return STAR_ATTN_ERR_MISALIGNED;
   SplitPlan plan;
-  if (!make_plan(shape, q_len, cache_len + q_len, O_part != nullptr, &plan))
+  if (!make_plan(shape, q_len, total, O_part != nullptr, &plan))
     return STAR_ATTN_ERR_INVALID_SHAPE;
   if (workspace_bytes < plan_bytes(shape, plan, q_len)) return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
   Geom g = make_geom(shape);
@@ -329,8 +339,10 @@ static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t c
   // Kq/Vq and writes them to the cache); the other paths use the cache writer.
   // Unrotated keys cannot take the fused route (the decode kernel moves rows with
   // DMAs): they are rotated into the cache first.
-  const bool fused_append = shape->dtype == STAR_ATTN_BF16 && plan.decode && !rope;
-  if (rope) {
+  const bool fused_append = append && shape->dtype == STAR_ATTN_BF16 && plan.decode && !rope;
+  if (!append) {
+    // a context host's share: the cache is read as it is
+  } else if (rope) {
     const int64_t pos = rope->pos0 + cache_len;
     if (launch_rope_rotate(shape->dtype, g.B, q_len, g.Hq, g.d, pos, rope->theta, Qq, Qq, st) !=
             hipSuccess ||
@@ -347,6 +359,7 @@ static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t c
   size_t rows = (size_t)g.B * plan.s_total * g.Hq * (size_t)q_len;
   Phase2Args a;
   a.g = g; a.plan = plan; a.cache_len = cache_len; a.q_len = (int32_t)q_len;
+  a.causal = append ? 1 : 0;
   a.Qq = Qq; a.Kc = K_cache; a.Vc = V_cache;
   a.Kn = fused_append ? Kq : nullptr;
   a.Vn = fused_append ? Vq : nullptr;
@@ -360,7 +373,12 @@ static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t c
 
   MergeArgs m;
   m.g = g; m.plan = plan; m.q_len = (int32_t)q_len; m.out_bf16 = shape->dtype == STAR_ATTN_BF16;
-  m.O_sub = a.O_sub; m.LSE_sub = a.LSE_sub; m.O_part = O_part; m.LSE_part = LSE_part; m.O = O;
+  m.O_sub = a.O_sub; m.LSE_sub = a.LSE_sub; m.O_part = O_part; m.LSE_part = LSE_part;
+  m.batch_stride = (int64_t)plan.s_total * g.Hq * q_len;
+  m.split_stride = (int64_t)g.Hq * q_len;
+  m.O = pair ? nullptr : O;
+  m.A = pair ? A : nullptr;
+  m.LSE = pair ? LSE : nullptr;
   return launch_merge(m, st) == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
 }
 
@@ -371,7 +389,46 @@ int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_
                      void* K_cache, void* V_cache, float* O_part, float* LSE_part, void* O,
                      void* workspace, size_t workspace_bytes, void* hip_stream) {
   return phase2_impl(shape, nullptr, cache_len, q_len, const_cast<void*>(Qq), Kq, Vq, K_cache,
-                     V_cache, O_part, LSE_part, O, workspace, workspace_bytes, hip_stream);
+                     V_cache, O_part, LSE_part, O, false, nullptr, nullptr, workspace,
+                     workspace_bytes, hip_stream);
+}
+
+int star_attn_phase2_partial(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
+                             const void* Qq, const void* Kq, const void* Vq, void* K_cache,
+                             void* V_cache, float* A, float* LSE, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  if ((Kq == nullptr) != (Vq == nullptr)) return STAR_ATTN_ERR_NULL_POINTER;
+  return phase2_impl(shape, nullptr, cache_len, q_len, const_cast<void*>(Qq), Kq, Vq, K_cache,
+                     V_cache, nullptr, nullptr, nullptr, true, A, LSE, workspace, workspace_bytes,
+                     hip_stream);
+}
+
+int star_attn_merge(const star_attn_shape* shape, int64_t n_parts, int64_t q_len,
+                    const float* A_parts, const float* LSE_parts, void* O, float* A, float* LSE,
+                    void* hip_stream) {
+  int rc = validate_shape(shape);
+  if (rc != STAR_ATTN_OK) return rc;
+  if (n_parts <= 0 || n_parts > (1 << 20) || q_len <= 0 || q_len > (1 << 20))
+    return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (!A_parts || !LSE_parts || (!O && !A)) return STAR_ATTN_ERR_NULL_POINTER;
+  if (misaligned(A_parts) || ((uintptr_t)LSE_parts & 3u) || misaligned(O) || misaligned(A) ||
+      ((uintptr_t)LSE & 3u))
+    return STAR_ATTN_ERR_MISALIGNED;
+  Geom g = make_geom(shape);
+  const int64_t rows = (int64_t)g.B * g.Hq * q_len;
+  if (rows > (int64_t)0x7fffffff || rows * n_parts > ((int64_t)1 << 40)) return STAR_ATTN_ERR_INVALID_SHAPE;
+  MergeArgs m;
+  m.g = g;
+  m.plan = SplitPlan{0, 0, 0, 0, (int32_t)n_parts, 0, 1};    // one part made of n_parts splits
+  m.q_len = (int32_t)q_len;
+  m.out_bf16 = shape->dtype == STAR_ATTN_BF16;
+  m.O_sub = A_parts; m.LSE_sub = LSE_parts;
+  m.batch_stride = (int64_t)g.Hq * q_len;                    // [n_parts, B, Hq, q_len, d]
+  m.split_stride = rows;
+  m.O_part = nullptr; m.LSE_part = nullptr;
+  m.O = O; m.A = A; m.LSE = LSE;
+  return launch_merge(m, (hipStream_t)hip_stream) == hipSuccess ? STAR_ATTN_OK
+                                                                : STAR_ATTN_ERR_LAUNCH_FAILED;
 }
 
 int star_attn_phase2_rope(const star_attn_shape* shape, double rope_theta, int64_t pos0,
@@ -381,7 +438,7 @@ int star_attn_phase2_rope(const star_attn_shape* shape, double rope_theta, int64
                           void* hip_stream) {
   Rope rope = {rope_theta, pos0};
   return phase2_impl(shape, &rope, cache_len, q_len, Qq, Kq, Vq, K_cache, V_cache, O_part,
-                     LSE_part, O, workspace, workspace_bytes, hip_stream);
+                     LSE_part, O, false, nullptr, nullptr, workspace, workspace_bytes, hip_stream);
 }
 
 const char* star_attn_status_string(int status) {

@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   const bool live = qc < R;
 
   const int cache_len = (int)a.cache_len;
-  const int total = cache_len + a.q_len;
+  const int total = (int)visible_total(a);
   // step `cur` of this split covers keys [base + cur * stride, +32) below hi
   int base, stride, nsteps, hi;
   if (a.plan.flat) {
@@ -291,11 +291,12 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
     voff[it] = (4 * it + (lane >> 4)) * ROWB + (((lane & 15) ^ swz(4 * it + (lane >> 4))) << 4);
 
   const float c = g.scale * LOG2E;
-  // token j sees rows [0, cache_len + j]; keys below free_hi are visible to every
+  // keys below free_hi (what the call's first token sees) are visible to every
   // live column, so only steps reaching past it take the masking path
-  const int row_lim = live ? cache_len + j + 1 : 0;
+  const int row_lim = live ? (int)visible_limit(a, j) : 0;
   const int lim = row_lim < hi ? row_lim : hi;
-  const int free_hi = cache_len + 1 < hi ? cache_len + 1 : hi;
+  const int first_lim = (int)visible_limit(a, 0);
+  const int free_hi = first_lim < hi ? first_lim : hi;
 
   // ring slot of step s is s % RING; AHEAD = RING - 1 steps are in flight while
   // one is consumed

@@ -715,7 +715,7 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase2_rows_bf16_kernel(P
   int beta = id / a.plan.s_total;
   int kvh = blockIdx.y;
 
-  int total = (int)(a.cache_len + a.q_len);
+  int total = (int)visible_total(a);
   int64_t lo64, hi64;
   split_range(a.plan, g.L, g.b, total, sp, &lo64, &hi64);
   int lo = (int)lo64, hi = (int)hi64;
@@ -726,7 +726,6 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase2_rows_bf16_kernel(P
   int head[RB], jrow[RB], row_lim[RB];
   bool active[RB];
   int wave_lo = 0x7fffffff;
-  const int cl = (int)a.cache_len;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     int gb = wave * RB + rb;
@@ -736,9 +735,8 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase2_rows_bf16_kernel(P
     active[rb] = jrow[rb] < a.q_len;
     int qj = active[rb] ? jrow[rb] : (j0 < a.q_len ? j0 : a.q_len - 1);
     load_q(w, rb, (const char*)a.Qq + (((size_t)beta * a.q_len + qj) * g.Hq + head[rb]) * ROWB, j4);
-    // token j sees cache rows [0, cache_len + j]
-    row_lim[rb] = active[rb] ? cl + jrow[rb] + 1 : 0;
-    int l0 = j0 < a.q_len ? cl + j0 + 1 : 0;
+    row_lim[rb] = active[rb] ? (int)visible_limit(a, jrow[rb]) : 0;
+    int l0 = j0 < a.q_len ? (int)visible_limit(a, j0) : 0;
     wave_lo = l0 < wave_lo ? l0 : wave_lo;
   }
   wave_lo = __builtin_amdgcn_readfirstlane(wave_lo);   // wave-uniform

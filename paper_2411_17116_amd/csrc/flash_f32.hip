@@ -179,7 +179,7 @@ __global__ __launch_bounds__(ROWS) void phase2_f32_kernel(Phase2Args a, int row_
   int beta = bs / a.plan.s_total, s = bs % a.plan.s_total;
   int j = (blockIdx.x % row_tiles) * ROWS + threadIdx.x;
   bool active = j < a.q_len;
-  int64_t total = a.cache_len + a.q_len;
+  int64_t total = visible_total(a);
   int64_t lo, hi;
   split_range(a.plan, g.L, g.b, total, s, &lo, &hi);
   int kvh = h / g.G;
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(ROWS) void phase2_f32_kernel(Phase2Args a, int row_
   RowState<D> st;
   load_row<D>(st, (const float*)a.Qq + (((int64_t)beta * a.q_len + (active ? j : 0)) * g.Hq + h) * D,
               active, g.scale * LOG2E);
-  int64_t limit = active ? a.cache_len + j + 1 : 0;   // token j sees rows [0, cache_len + j]
+  int64_t limit = active ? visible_limit(a, j) : 0;
   attend_range<D>(st, Kb, Vb, lo, hi, limit, Ks, Vs);
   if (active) {
     int64_t r = (((int64_t)beta * a.plan.s_total + s) * g.Hq + h) * a.q_len + j;

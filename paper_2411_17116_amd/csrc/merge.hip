@@ -8,15 +8,19 @@
 //     lse' = logaddexp(lse, lse_m),  O' = exp(lse - lse') O + exp(lse_m - lse') A_m,
 // which is what Eq. 3-4 evaluate to.  An empty split or part has lse = -inf and
 // weight 0.  Under a flat split plan everything is one part.  The order of every
-// fold is fixed, so results are deterministic.
+// fold is fixed, so results are deterministic.  The same kernel is the query
+// host's aggregation of the pairs gathered from other hosts (Algorithm 2): the
+// hosts' pairs are the splits of one part.  Besides the output in the storage
+// dtype it can leave the merged pair itself, (A, lse) in fp32 -- what a host
+// sends when its cache is one share of a larger one.
 //
 // One workgroup per (batch, head, row): GROUPS groups of 32 lanes walk the
 // splits of a part, each lane owning d/32 output elements and each group
 // folding its splits with a running maximum (loads of INFL splits are in flight
 // per group); the partial results are combined through LDS.  A decode step has
-// few rows and hundreds of splits per row (16 groups x 8 in flight: four round
-// trips for 512 splits); a query-encode call has thousands of rows and a few
-// splits per part (8 groups x 4).  Traffic is s_total * (d + 1) floats per row
+// few rows and 64 to 512 splits per row (16 groups x 8 in flight: one to four
+// round trips); a query-encode call has thousands of rows and a few splits per
+// part (8 groups x 4).  Traffic is s_total * (d + 1) floats per row
 // -- negligible next to the cache.
 #include "star_internal.h"
 
@@ -45,8 +49,8 @@ __global__ __launch_bounds__(32 * GROUPS) void merge_kernel(MergeArgs a) {
   int h = (int)((row / a.q_len) % g.Hq);
   int beta = (int)(row / ((int64_t)a.q_len * g.Hq));
   const SplitPlan& p = a.plan;
-  const int64_t sub_stride = (int64_t)g.Hq * a.q_len;                       // rows between splits
-  const int64_t base = ((int64_t)beta * p.s_total * g.Hq + h) * a.q_len + j; // split 0
+  const int64_t sub_stride = a.split_stride;                                 // rows between splits
+  const int64_t base = (int64_t)beta * a.batch_stride + (int64_t)h * a.q_len + j;   // split 0
   const int n_parts = p.flat ? 1 : p.n_blocks + 1;
 
   float m_g = -INFINITY, l_g = 0.f;
@@ -140,12 +144,16 @@ __global__ __launch_bounds__(32 * GROUPS) void merge_kernel(MergeArgs a) {
   }
   if (grp == 0) {
     int64_t orow = ((int64_t)beta * a.q_len + j) * g.Hq + h;
+    int64_t arow = ((int64_t)beta * g.Hq + h) * a.q_len + j;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       float out = l_g > 0.f ? acc_g[e] / l_g : 0.f;
+      if (a.A) a.A[arow * D + li * E + e] = out;
+      if (!a.O) continue;
       if (a.out_bf16) ((unsigned short*)a.O)[orow * D + li * E + e] = f32_to_bf16_rne(out);
       else ((float*)a.O)[orow * D + li * E + e] = out;
     }
+    if (a.LSE && li == 0) a.LSE[arow] = l_g > 0.f ? m_g + logf(l_g) : -INFINITY;
   }
 }
 
@@ -153,7 +161,8 @@ __global__ __launch_bounds__(32 * GROUPS) void merge_kernel(MergeArgs a) {
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st) {
   int64_t rows = (int64_t)a.g.B * a.g.Hq * a.q_len;
-  const bool wide = a.plan.flat != 0;      // decode: few rows, hundreds of splits each
+  // decode: few rows, many splits each
+  const bool wide = a.plan.flat != 0 && a.plan.s_total > 32;
   if (a.g.d == 64) merge_kernel<64, 8, 4><<<dim3((unsigned)rows), 256, 0, st>>>(a);
   else if (wide) merge_kernel<128, 16, 8><<<dim3((unsigned)rows), 512, 0, st>>>(a);
   else merge_kernel<128, 8, 4><<<dim3((unsigned)rows), 256, 0, st>>>(a);

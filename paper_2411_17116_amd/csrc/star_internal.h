@@ -40,7 +40,10 @@ struct Geom {
 
 // What prefixes a context block after the first (values of the public
 // STAR_ATTN_ANCHOR_* constants).
-enum AnchorMode { ANCHOR_FIRST = 0, ANCHOR_PREVIOUS = 1, ANCHOR_EXTERNAL = 2, ANCHOR_PER_BLOCK = 3 };
+enum AnchorMode {
+  ANCHOR_FIRST = 0, ANCHOR_PREVIOUS = 1, ANCHOR_EXTERNAL = 2, ANCHOR_PER_BLOCK = 3,
+  ANCHOR_ALL_BLOCKS = 4   // the call is a host's share: its first block is prefixed too
+};
 
 struct Phase1Args {
   Geom g;
@@ -50,8 +53,8 @@ struct Phase1Args {
   const void* Kc;       // caches [B, Hkv, cap, d], already holding the context
   const void* Vc;
   int32_t anchor_mode;  // AnchorMode
-  const void* Ka;       // ANCHOR_EXTERNAL / PER_BLOCK: anchor keys / values of n_anchor =
-  const void* Va;       // 1 / n anchors; head-major [B, Hkv, n_anchor * a, d] for the fp32
+  const void* Ka;       // ANCHOR_EXTERNAL / ALL_BLOCKS / PER_BLOCK: anchor keys / values of n_anchor
+  const void* Va;       // = 1 / 1 / n anchors; head-major [B, Hkv, n_anchor * a, d] for the fp32
                         // kernel, token-major [B, n_anchor, a, Hkv, d] for the bf16 one
   const void* Kin;      // bf16 kernel: the token-major inputs [B, L, Hkv, d] to read keys /
   const void* Vin;      // values from (and to file in the caches); null: read the caches
@@ -59,14 +62,15 @@ struct Phase1Args {
 
 // Anchor key rows [*lo, *hi) of 0-based block i, and whether they index the
 // external anchor buffers (true; rows counted over all of a batch's anchors) or
-// the context keys (false).  Block 0 has none.
+// the context keys (false).  Block 0 has none, unless the call's context is a
+// host's share that starts after the global first block (ANCHOR_ALL_BLOCKS).
 __host__ __device__ inline bool anchor_range(const Geom& g, int mode, int64_t i, int64_t* lo,
                                              int64_t* hi) {
-  if (i == 0 || g.a == 0) { *lo = 0; *hi = 0; return false; }
+  if (g.a == 0 || (i == 0 && mode != ANCHOR_ALL_BLOCKS)) { *lo = 0; *hi = 0; return false; }
   if (mode == ANCHOR_PREVIOUS) { *lo = i * g.b - g.a; *hi = i * g.b; return false; }
   if (mode == ANCHOR_PER_BLOCK) { *lo = i * g.a; *hi = (i + 1) * g.a; return true; }
   *lo = 0; *hi = g.a;
-  return mode == ANCHOR_EXTERNAL;
+  return mode == ANCHOR_EXTERNAL || mode == ANCHOR_ALL_BLOCKS;
 }
 
 struct Phase2Args {
@@ -74,6 +78,8 @@ struct Phase2Args {
   SplitPlan plan;
   int64_t cache_len;    // tokens cached before this call
   int32_t q_len;
+  int32_t causal;       // 1: the new tokens are appended and token j sees rows [0, cache_len + j];
+                        // 0: nothing is appended and every token sees rows [0, cache_len)
   const void* Qq;       // [B, q_len, Hq, d]
   const void* Kn;       // new tokens' K, V [B, q_len, Hkv, d]; null: the caches already
   const void* Vn;       // hold them (decode kernel: nothing to append, read the caches)
@@ -83,6 +89,17 @@ struct Phase2Args {
   float* LSE_sub;       // [B, s_total, Hq, q_len]      per-split log-sum-exp
 };
 
+// Cache rows a phase-2 call may see in all, and new token j's exclusive bound.
+__host__ __device__ inline int64_t visible_total(const Phase2Args& a) {
+  return a.cache_len + (a.causal ? a.q_len : 0);
+}
+__host__ __device__ inline int64_t visible_limit(const Phase2Args& a, int j) {
+  return a.causal ? a.cache_len + j + 1 : a.cache_len;
+}
+
+// Split s of (batch beta, head h, token j) is row
+//   beta * batch_stride + s * split_stride + h * q_len + j
+// of O_sub (d floats per row) and LSE_sub.
 struct MergeArgs {
   Geom g;
   SplitPlan plan;
@@ -90,9 +107,13 @@ struct MergeArgs {
   int32_t out_bf16;
   const float* O_sub;
   const float* LSE_sub;
+  int64_t batch_stride;
+  int64_t split_stride;
   float* O_part;        // [B, n+1, Hq, q_len, d] or null
   float* LSE_part;      // [B, n+1, Hq, q_len] or null
-  void* O;              // [B, q_len, Hq, d]
+  void* O;              // [B, q_len, Hq, d] in the storage dtype, or null
+  float* A;             // the same result in fp32, [B, Hq, q_len, d] (Eq. 1 of everything
+  float* LSE;           // merged), and its log-sum-exp [B, Hq, q_len]; each may be null
 };
 
 // Key range [lo, hi) of split s of a plan that is not flat (hi clipped to what

@@ -41,7 +41,8 @@ def test_header_symbols_are_exported(lib):
     assert set(names) >= {"star_attn_phase1", "star_attn_phase2", "star_attn_workspace_bytes",
                           "star_attn_status_string", "star_attn_kernel_path",
                           "star_attn_phase1_anchor", "star_attn_phase1_workspace_bytes",
-                          "star_attn_phase1_rope", "star_attn_phase2_rope", "star_attn_rope"}
+                          "star_attn_phase1_rope", "star_attn_phase2_rope", "star_attn_rope",
+                          "star_attn_phase2_partial", "star_attn_merge"}
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -164,7 +165,7 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
 def test_phase1_anchor_variant_arguments(lib):
     shape = good_shape()
     EXT = binding.ANCHOR_EXTERNAL
-    for mode in (-1, 4, 99):
+    for mode in (-1, 5, 99):
         assert _p1a(lib, shape, mode) == ERR["INVALID_MODE"]
     assert _p1a(lib, good_shape(anchor=300), binding.ANCHOR_PREVIOUS) == ERR["ANCHOR_GT_BLOCK"]
     for mode in (binding.ANCHOR_FIRST, binding.ANCHOR_PREVIOUS, EXT):
@@ -191,6 +192,55 @@ def test_phase1_anchor_variant_arguments(lib):
     assert _p1a(lib, f32, EXT, ws=None, ws_bytes=need) == ERR["NULL_POINTER"]
     assert _p1a(lib, f32, EXT, ws=0x1010, ws_bytes=need) == ERR["MISALIGNED"]
     assert _p1a(lib, f32, EXT, ws_bytes=need - 1) == ERR["WORKSPACE_TOO_SMALL"]
+    # a host's share takes one anchor, like EXTERNAL
+    ALL = binding.ANCHOR_ALL_BLOCKS
+    assert sa.binding.phase1_workspace_bytes(f32, ALL) == need
+    assert sa.binding.phase1_workspace_bytes(shape, ALL) == 0
+    assert _p1a(lib, shape, ALL, Ka=None) == ERR["NULL_POINTER"]
+    assert _p1a(lib, shape, ALL, Va=0x1008) == ERR["MISALIGNED"]
+    assert _p1a(lib, f32, ALL, ws_bytes=need - 1) == ERR["WORKSPACE_TOO_SMALL"]
+
+
+def test_host_share_entry_point_arguments(lib):
+    """star_attn_phase2_partial and star_attn_merge validate on the host."""
+    shape = good_shape()
+    L, cap = shape.ctx_len, shape.cache_capacity
+
+    def part(cache_len=L, q_len=1, Qq=0x1000, Kq=None, Vq=None, Kc=0x1000, Vc=0x1000, A=0x1000,
+             LSE=0x1000, ws=0x1000, ws_bytes=64):
+        return lib.star_attn_phase2_partial(ctypes.byref(shape), cache_len, q_len, Qq, Kq, Vq, Kc, Vc,
+                                            A, LSE, ws, ws_bytes, None)
+
+    assert part() == ERR["WORKSPACE_TOO_SMALL"]                     # valid up to the workspace
+    assert part(Kq=0x1000, Vq=0x1000) == ERR["WORKSPACE_TOO_SMALL"]
+    assert part(Kq=0x1000) == ERR["NULL_POINTER"]                   # K without V
+    assert part(Vq=0x1000) == ERR["NULL_POINTER"]
+    assert part(A=None) == ERR["NULL_POINTER"]
+    assert part(LSE=None) == ERR["NULL_POINTER"]
+    assert part(Qq=None) == ERR["NULL_POINTER"]
+    assert part(A=0x1004) == ERR["MISALIGNED"]
+    assert part(LSE=0x1002) == ERR["MISALIGNED"]
+    assert part(q_len=0) == ERR["INVALID_SHAPE"]
+    assert part(cache_len=L - 1) == ERR["INVALID_SHAPE"]
+    # a context host may read a full cache; the query host needs room to append
+    assert part(cache_len=cap) == ERR["WORKSPACE_TOO_SMALL"]
+    assert part(cache_len=cap + 1) == ERR["CACHE_OVERFLOW"]
+    assert part(cache_len=cap, Kq=0x1000, Vq=0x1000) == ERR["CACHE_OVERFLOW"]
+
+    def mrg(n_parts=3, q_len=2, Ap=0x1000, Lp=0x1000, O=0x1000, A=None, LSE=None, sh=shape):
+        return lib.star_attn_merge(ctypes.byref(sh), n_parts, q_len, Ap, Lp, O, A, LSE, None)
+
+    assert mrg(n_parts=0) == ERR["INVALID_SHAPE"]
+    assert mrg(q_len=0) == ERR["INVALID_SHAPE"]
+    assert mrg(n_parts=(1 << 20) + 1) == ERR["INVALID_SHAPE"]
+    assert mrg(Ap=None) == ERR["NULL_POINTER"]
+    assert mrg(Lp=None) == ERR["NULL_POINTER"]
+    assert mrg(O=None) == ERR["NULL_POINTER"]                       # neither O nor A
+    assert mrg(Ap=0x1004) == ERR["MISALIGNED"]
+    assert mrg(O=0x1008) == ERR["MISALIGNED"]
+    assert mrg(O=None, A=0x1008) == ERR["MISALIGNED"]
+    assert mrg(LSE=0x1001) == ERR["MISALIGNED"]
+    assert mrg(sh=good_shape(head_dim=96)) == ERR["UNSUPPORTED_HEAD_DIM"]
 
 
 def test_rope_entry_point_arguments(lib):
@@ -248,6 +298,8 @@ def test_header_is_plain_c(tmp_path):
         "  rc |= star_attn_phase1_rope(&s, 10000.0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
         "  rc |= star_attn_phase2_rope(&s, 10000.0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
         "  rc |= star_attn_rope(&s, 1, 1, 0, 10000.0, 0, 0, 0);\n"
+        "  rc |= star_attn_phase2_partial(&s, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
+        "  rc |= star_attn_merge(&s, 1, 1, 0, 0, 0, 0, 0, 0);\n"
         "  return (rc != 0 && star_attn_workspace_bytes(&s, 1) == 0 &&\n"
         "          star_attn_phase1_workspace_bytes(&s, 0) == 0 &&\n"
         "          star_attn_status_string(rc) != 0 && star_attn_kernel_path(&s) == 0) ? 0 : 1;\n"
