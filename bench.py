@@ -358,6 +358,60 @@ def anchor_variants(cfg, shape, inp, bufs):
     return out
 
 
+def host_share(cfg, inp):
+    """One host's share when every context block lives on its own host (the
+    paper's deployment: n hosts, one block each): phase 1 of a context host
+    ([anchor; block]) and of the first host (its block alone), a context host's
+    and the query host's pair for one decode step, and the merge of the n
+    gathered pairs.  Times of single calls on this GPU; no exchange is timed."""
+    n, b, a = cfg.n_blocks, cfg.b, cfg.a
+    tail = cfg.lq + cfg.nd
+    dev = inp.Q.device
+    hshape = sa.StarShape.make(cfg.dtype, cfg.B, cfg.Hq, cfg.Hkv, cfg.d, b, b, a, b + tail)
+    Kc, Vc = sa.alloc_cache(hshape)
+    ws = sa.alloc_workspace(hshape, 1)
+    Q, K, V = (x[:, b:2 * b].contiguous() for x in (inp.Q, inp.K, inp.V))
+    Q0, K0, V0 = (x[:, :b].contiguous() for x in (inp.Q, inp.K, inp.V))
+    Ka, Va = K0[:, :a].contiguous(), V0[:, :a].contiguous()
+    O = torch.empty_like(Q)
+    t = Timer()
+
+    def best(fn, reps=5):
+        idx = []
+        for _ in range(reps):
+            e = t.start()
+            fn()
+            idx.append(t.stop(e))
+        torch.cuda.synchronize()
+        return min(t.ms(i) for i in idx[1:])
+
+    first_ms = best(lambda: sa.phase1(hshape, Q0, K0, V0, O, Kc, Vc), 3)
+    ctx_ms = best(lambda: sa.phase1_anchor(hshape, sa.ANCHOR_ALL_BLOCKS, Q, K, V, O, Kc, Vc,
+                                           K_anchor=Ka, V_anchor=Va), 3)
+    pairs = a * b + b * (b + 1) // 2
+    flops = 4.0 * cfg.d * cfg.Hq * cfg.B * pairs
+    Qd, Kd, Vd = (x[:, :1].contiguous() for x in (inp.Qd, inp.Kd, inp.Vd))
+    A = torch.empty((n, cfg.B, cfg.Hq, 1, cfg.d), dtype=torch.float32, device=dev)
+    L = torch.empty((n, cfg.B, cfg.Hq, 1), dtype=torch.float32, device=dev)
+    ctx_us = 1e3 * best(lambda: sa.phase2_partial(hshape, b, Qd, Kc, Vc, A[0], L[0], ws), 12)
+    qh_us = 1e3 * best(lambda: sa.phase2_partial(hshape, b + cfg.lq, Qd, Kc, Vc, A[1], L[1], ws,
+                                                 Kq=Kd, Vq=Vd), 12)
+    for i in range(2, n):
+        A[i].copy_(A[0])
+        L[i].copy_(L[0])
+    Od = torch.empty_like(Qd)
+    merge_us = 1e3 * best(lambda: sa.merge(hshape, A, L, O=Od), 12)
+    host_bytes = 2.0 * cfg.B * cfg.Hkv * cfg.d * 2 * b
+    return {"hosts": n, "tokens_per_host": b,
+            "phase1_context_host_ms": ctx_ms, "phase1_context_host_tflops": flops / (ctx_ms * 1e-3) / 1e12,
+            "phase1_first_host_ms": first_ms,
+            "decode_context_host_us": ctx_us, "decode_context_host_gb_per_s": host_bytes / (ctx_us * 1e-6) / 1e9,
+            "decode_query_host_us": qh_us, "merge_us": merge_us,
+            "note": "one host's calls at the shape it has when each of the n blocks sits on its own "
+                    "host: star_attn_phase1_anchor(ALL_BLOCKS), star_attn_phase2_partial, "
+                    "star_attn_merge of n pairs; single-call times, the exchange between hosts is not part of them"}
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summaries
     (profiles/traffic.json), or None if that kernel/workload was not profiled."""
@@ -381,6 +435,8 @@ def main():
                     help="skip the HIP-graph replay of the decode loop")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip timing the anchor variants of the ablation study")
+    ap.add_argument("--no-hosts", action="store_true",
+                    help="skip the timing of one host's share (per-host entry points)")
     ap.add_argument("--no-rope", action="store_true",
                     help="skip timing the entry points that take unrotated projections")
     ap.add_argument("--no-power", action="store_true",
@@ -501,6 +557,8 @@ def main():
         out["phase2"]["decode_graph"] = decode_graph(cfg, shape, bufs)
     if "phase1" in sections and not args.no_variants and cfg.dtype == "bf16" and cfg.name != "C4":
         out["anchor_variants"] = anchor_variants(cfg, shape, inp, bufs)
+    if sections == ("phase1", "query", "decode") and not args.no_hosts and cfg.dtype == "bf16":
+        out["host_share"] = host_share(cfg, inp)
     if "phase1" in sections and not args.no_rope:
         out["rope"] = rope_cost(cfg, shape, inp, bufs)
         # the caches now hold rotated keys; nothing below reads them
