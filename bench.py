@@ -412,6 +412,58 @@ def host_share(cfg, inp):
                     "star_attn_merge of n pairs; single-call times, the exchange between hosts is not part of them"}
 
 
+def ceilings(bufs):
+    """What this machine sustains for the two resources the rooflines name,
+    measured with the calibration kernels of libstarcalib.so: independent bf16
+    MFMAs on register operands (random bits, as attention has them, and constant
+    bits) held for about half a second each, so that the power limit has set the
+    clock, and a plain 16-byte-per-lane read of as many bytes as the K and V caches hold."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2411_17116_amd", "libstarcalib.so")
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not found: build it with `python -m paper_2411_17116_amd.build`")
+    lib = ctypes.CDLL(path)
+    vp = ctypes.c_void_p
+    lib.star_calib_seed_bytes.restype = ctypes.c_size_t
+    lib.star_calib_out_words.restype = ctypes.c_size_t
+    lib.star_calib_mfma_flops.restype = ctypes.c_double
+    lib.star_calib_mfma_flops.argtypes = [ctypes.c_int]
+    lib.star_calib_mfma.argtypes = [vp, vp, ctypes.c_int, vp]
+    lib.star_calib_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    out = torch.empty(lib.star_calib_out_words(), dtype=torch.float32, device="cuda")
+    n_seed = lib.star_calib_seed_bytes() // 2
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    seeds = {"random": torch.randn(n_seed, generator=gen, device="cuda").to(torch.bfloat16),
+             "constant": torch.ones(n_seed, dtype=torch.bfloat16, device="cuda")}
+    t = Timer()
+    res = {}
+    iters = 3_000_000
+    for name, seed in seeds.items():
+        idx = []
+        for _ in range(2):
+            e = t.start()
+            rc = lib.star_calib_mfma(vp(seed.data_ptr()), vp(out.data_ptr()), iters, stream)
+            idx.append(t.stop(e))
+            assert rc == 0
+        torch.cuda.synchronize()
+        res[f"mfma_{name}_operands_tflops"] = lib.star_calib_mfma_flops(iters) / (t.ms(idx[1]) * 1e-3) / 1e12
+    src = torch.cat([bufs["Kc"].view(-1), bufs["Vc"].view(-1)])   # as many bytes as a decode step reads
+    nbytes = src.numel() * src.element_size()
+    idx = []
+    for _ in range(6):
+        e = t.start()
+        rc = lib.star_calib_hbm_read(vp(src.data_ptr()), nbytes, vp(out.data_ptr()), stream)
+        idx.append(t.stop(e))
+        assert rc == 0
+    torch.cuda.synchronize()
+    res["hbm_read_gb_per_s"] = nbytes / (min(t.ms(i) for i in idx[1:]) * 1e-3) / 1e9
+    res["hbm_read_bytes"] = nbytes
+    res["note"] = ("calibration kernels (csrc/calib.hip): v_mfma_f32_16x16x32_bf16 only, 8 wavefronts per CU, "
+                   f"{iters} x 8 per wavefront per launch; grid-stride read of a copy of the K and V caches, best of 5")
+    return res
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summaries
     (profiles/traffic.json), or None if that kernel/workload was not profiled."""
@@ -435,6 +487,8 @@ def main():
                     help="skip the HIP-graph replay of the decode loop")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip timing the anchor variants of the ablation study")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the calibration kernels (sustained MFMA rate, plain HBM read)")
     ap.add_argument("--no-hosts", action="store_true",
                     help="skip the timing of one host's share (per-host entry points)")
     ap.add_argument("--no-rope", action="store_true",
@@ -557,6 +611,14 @@ def main():
         out["phase2"]["decode_graph"] = decode_graph(cfg, shape, bufs)
     if "phase1" in sections and not args.no_variants and cfg.dtype == "bf16" and cfg.name != "C4":
         out["anchor_variants"] = anchor_variants(cfg, shape, inp, bufs)
+    if not args.no_ceilings:
+        try:       # calibration only: its absence must not cost the run its result
+            c = ceilings(bufs)
+            out["roofline"]["frac_of_measured_mfma_rate"] = p1_tflops / c["mfma_random_operands_tflops"]
+            out["roofline_decode"]["frac_of_measured_hbm_read"] = dec_gbs / c["hbm_read_gb_per_s"]
+        except (OSError, AssertionError) as exc:
+            c = {"error": str(exc)}
+        out["ceilings"] = c
     if sections == ("phase1", "query", "decode") and not args.no_hosts and cfg.dtype == "bf16":
         out["host_share"] = host_share(cfg, inp)
     if "phase1" in sections and not args.no_rope:

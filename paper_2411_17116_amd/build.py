@@ -1,4 +1,5 @@
-"""Builds libstarattn.so (the C-ABI HIP library) in-tree with hipcc for gfx950.
+"""Builds libstarattn.so (the C-ABI HIP library) and libstarcalib.so (the
+benchmark's calibration kernels) in-tree with hipcc for gfx950.
 
 Usage:  python -m paper_2411_17116_amd.build
 The library is written next to this file so that it travels with the source
@@ -15,6 +16,10 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstarattn.so")
 SOURCES = ["api.hip", "kv_cache.hip", "rope.hip", "flash_f32.hip", "flash_bf16.hip",
            "decode_bf16.hip", "merge.hip"]
+# the benchmark's calibration kernels: a library of their own, so that the
+# product library holds nothing but the path
+CALIB_LIB = os.path.join(HERE, "libstarcalib.so")
+CALIB_SOURCES = ["calib.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -33,9 +38,10 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
-    for src in SOURCES:
+    for src in SOURCES + CALIB_SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        objs.append(obj)
+        if src in SOURCES:
+            objs.append(obj)
         cmd = [hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -59,6 +65,11 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    calib_objs = [os.path.join(objdir, src.replace(".hip", ".o")) for src in CALIB_SOURCES]
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *calib_objs, "-o", CALIB_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
