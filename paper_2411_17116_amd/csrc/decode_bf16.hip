@@ -135,7 +135,7 @@ __device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr
     s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      bf16x8 a = *(LDS_AS bf16x8*)(kaddr[t] + KOFF + kt * 16 * ROWB);
+      bf16x8 a = *(LDS_AS bf16x8*)(size_t)(kaddr[t] + KOFF + kt * 16 * ROWB);
       s[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, w.q[t], s[kt], 0, 0, 0);
     }
   }
@@ -176,8 +176,8 @@ __device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr
   // transposing reads.
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) {
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(vaddr[dt] + VOFF));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(vaddr[dt] + VOFF + 16 * ROWB));
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(size_t)(vaddr[dt] + VOFF));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(size_t)(vaddr[dt] + VOFF + 16 * ROWB));
     bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo), hi_b = __builtin_bit_cast(bf16x4, hi);
     bf16x8 a = __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
     w.o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, p, w.o[dt], 0, 0, 0);

@@ -89,13 +89,13 @@ __device__ __forceinline__ void dma16(const char* sbase, unsigned voff, unsigned
 }
 
 __device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
-  return *(LDS_AS bf16x8*)(addr);
+  return *(LDS_AS bf16x8*)(size_t)(addr);
 }
 
 // Transposing LDS read: within each group of 16 lanes, lane i receives element
 // i%4 of the four 8-byte rows addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.
 __device__ __forceinline__ bf16x4 lds_read_tr16(unsigned addr) {
-  return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(addr)));
+  return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(size_t)(addr)));
 }
 
 // The four lanes l, l^16, l^32, l^48 hold the keys of one query row.
