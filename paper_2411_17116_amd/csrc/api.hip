@@ -42,9 +42,10 @@ static int64_t ceil_div(int64_t x, int64_t y) { return (x + y - 1) / y; }
 static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
 
 // Workgroups of the decode kernel that are resident at once on an MI355X:
-// 256 CUs x 2 (the kernel's 64 KiB LDS ring allows two per CU).
+// 256 CUs x 4 (one single-wavefront workgroup per SIMD; its 32 KiB LDS ring
+// allows that many per CU).
 #ifndef STAR_DECODE_WGS_PER_CU
-#define STAR_DECODE_WGS_PER_CU 2
+#define STAR_DECODE_WGS_PER_CU 4
 #endif
 constexpr int64_t DECODE_SLOTS = 256 * STAR_DECODE_WGS_PER_CU;
 

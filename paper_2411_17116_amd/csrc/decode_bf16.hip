@@ -11,9 +11,12 @@
 //     read one contiguous window of its cache (every memory channel busy, none
 //     hot); with per-part outputs a split is a contiguous run inside one part;
 //   * the wavefront DMAs 32-key steps of K and V (8 KiB each) straight into a
-//     four-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
+//     two-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
 //     bursts, no VGPRs held by data in flight -- and waits with partial vmcnt so
-//     that three steps (48 KiB) are in flight while one is consumed;
+//     that one step (16 KiB) is in flight while one is consumed; 32 KiB of LDS
+//     per workgroup lets four of them share a CU, one per SIMD (measured: four
+//     wavefronts with one step ahead each stream 2 % faster than two with three
+//     ahead, one wavefront per CU 15 % slower);
 //   * all G query heads of the KV group (and up to 16/G new tokens) form the 16
 //     columns of v_mfma_f32_16x16x32_bf16, so K and V are read once per KV head;
 //     S^T = K Q^T leaves each lane with keys of one query column, and the
@@ -43,7 +46,7 @@ constexpr int ROWB = D * 2;
 constexpr int STEP = 32;                 // keys per pipeline step
 constexpr int STEPB = STEP * ROWB;       // 8 KiB of K (and of V) per step
 #ifndef STAR_DECODE_RING
-#define STAR_DECODE_RING 4
+#define STAR_DECODE_RING 2
 #endif
 constexpr int RING = STAR_DECODE_RING;   // steps in the LDS ring
 constexpr float LOG2E = 1.4426950408889634f;

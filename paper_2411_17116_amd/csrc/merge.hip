@@ -18,8 +18,8 @@
 // splits of a part, each lane owning d/32 output elements and each group
 // folding its splits with a running maximum (loads of INFL splits are in flight
 // per group); the partial results are combined through LDS.  A decode step has
-// few rows and 64 to 512 splits per row (16 groups x 8 in flight: one to four
-// round trips); a query-encode call has thousands of rows and a few splits per
+// few rows and 128 to 1024 splits per row (16 groups x 8 in flight: one to
+// eight round trips); a query-encode call has thousands of rows and a few splits per
 // part (8 groups x 4).  Traffic is s_total * (d + 1) floats per row
 // -- negligible next to the cache.
 #include "star_internal.h"
