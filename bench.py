@@ -358,6 +358,32 @@ def anchor_variants(cfg, shape, inp, bufs):
     return out
 
 
+def block_sweep(cfg, inp, bufs):
+    """Phase 1 against the block size, anchor = block, context length fixed:
+    the speed side of the paper's accuracy / speed trade-off (Section 3.4; the
+    method's cost is linear in the block size, full causal attention is the
+    last point)."""
+    out = []
+    t = Timer()
+    L = cfg.L
+    full_ms = None
+    for div in (1, 2, 4, 8, 16, 32):
+        b = L // div
+        shape = sa.StarShape.make(cfg.dtype, cfg.B, cfg.Hq, cfg.Hkv, cfg.d, L, b, b, cfg.cache_capacity)
+        idx = []
+        for _ in range(2):
+            e = t.start()
+            sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+            idx.append(t.stop(e))
+        torch.cuda.synchronize()
+        ms = min(t.ms(i) for i in idx)
+        full_ms = ms if div == 1 else full_ms
+        flops = phase1_flops(cfg, b=b, a=b)
+        out.append({"block": b, "n_blocks": div, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+                    "speedup_vs_full_causal": full_ms / ms})
+    return out
+
+
 def host_share(cfg, inp):
     """One host's share when every context block lives on its own host (the
     paper's deployment: n hosts, one block each): phase 1 of a context host
@@ -487,6 +513,8 @@ def main():
                     help="skip the HIP-graph replay of the decode loop")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip timing the anchor variants of the ablation study")
+    ap.add_argument("--no-block-sweep", action="store_true",
+                    help="skip phase 1 at other block sizes (the trade-off curve)")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the calibration kernels (sustained MFMA rate, plain HBM read)")
     ap.add_argument("--no-hosts", action="store_true",
@@ -611,6 +639,8 @@ def main():
         out["phase2"]["decode_graph"] = decode_graph(cfg, shape, bufs)
     if "phase1" in sections and not args.no_variants and cfg.dtype == "bf16" and cfg.name != "C4":
         out["anchor_variants"] = anchor_variants(cfg, shape, inp, bufs)
+    if "phase1" in sections and not args.no_block_sweep and cfg.dtype == "bf16" and cfg.name != "C4":
+        out["block_sweep"] = block_sweep(cfg, inp, bufs)
     if not args.no_ceilings:
         try:       # calibration only: its absence must not cost the run its result
             c = ceilings(bufs)

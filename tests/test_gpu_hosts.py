@@ -218,3 +218,32 @@ def test_config3_shape_on_eight_hosts_sampled():
     assert np.abs(O_dec.float().cpu().numpy() - ref["O"]).max() <= tol["o"]
     assert np.abs(torch.cat(lses, dim=2).cpu().numpy() - ref["LSE"]).max() <= tol["lse"]
     print("[hosts C3] decode parity on 3 steps, all heads", flush=True)
+
+
+def _cluster_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for k in range(n):
+        dtype = "bf16" if k % 3 else "fp32"
+        Hkv = int(rng.choice([1, 2]))
+        G = int(rng.choice([1, 2, 4, 8])) if dtype == "bf16" else int(rng.choice([1, 2]))
+        L = int(rng.choice([65, 200, 513, 1100, 1900]))
+        b = int(rng.choice([16, 63, 100, 256, 700]))
+        a = int(rng.integers(0, b + 1))
+        lq = int(rng.choice([1, 3, 16, 17, 40]))
+        nd = int(rng.choice([1, 2]))
+        n_blocks = -(-L // b)
+        n_hosts = int(rng.integers(1, min(n_blocks, 9) + 3))
+        owners = [h for h, (i0, i1) in enumerate(sh.block_runs(n_blocks, n_hosts)) if i1 > i0]
+        qh = int(rng.choice(owners))
+        d = 128 if dtype == "bf16" else 64
+        out.append(pytest.param(dtype, Hkv * G, Hkv, d, L, b, a, lq, nd, n_hosts, qh, 7000 + 10 * seed + k,
+                                id=f"{dtype}-H{Hkv * G}/{Hkv}-L{L}-b{b}-a{a}-lq{lq}-hosts{n_hosts}-q{qh}"))
+    return out
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,L,b,a,lq,nd,n_hosts,qh,seed", _cluster_cases(12, 3))
+def test_random_clusters(dtype, Hq, Hkv, d, L, b, a, lq, nd, n_hosts, qh, seed):
+    """Seeded random shapes, host counts and query hosts, every row."""
+    cfg = workloads.StarConfig("hosts-fuzz", dtype, 1, Hq, Hkv, d, L, b, a, lq, nd, seed=seed, n_planted=2)
+    _run_small(cfg, n_hosts, qh)
