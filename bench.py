@@ -455,7 +455,7 @@ def ceilings(bufs):
     lib.star_calib_mfma_flops.restype = ctypes.c_double
     lib.star_calib_mfma_flops.argtypes = [ctypes.c_int]
     lib.star_calib_mfma.argtypes = [vp, vp, ctypes.c_int, vp]
-    lib.star_calib_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.star_calib_hbm_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, vp]
     stream = vp(torch.cuda.current_stream().cuda_stream)
     out = torch.empty(lib.star_calib_out_words(), dtype=torch.float32, device="cuda")
     n_seed = lib.star_calib_seed_bytes() // 2
@@ -476,17 +476,18 @@ def ceilings(bufs):
         res[f"mfma_{name}_operands_tflops"] = lib.star_calib_mfma_flops(iters) / (t.ms(idx[1]) * 1e-3) / 1e12
     src = torch.cat([bufs["Kc"].view(-1), bufs["Vc"].view(-1)])   # as many bytes as a decode step reads
     nbytes = src.numel() * src.element_size()
-    idx = []
-    for _ in range(6):
-        e = t.start()
-        rc = lib.star_calib_hbm_read(vp(src.data_ptr()), nbytes, vp(out.data_ptr()), stream)
-        idx.append(t.stop(e))
-        assert rc == 0
-    torch.cuda.synchronize()
-    res["hbm_read_gb_per_s"] = nbytes / (min(t.ms(i) for i in idx[1:]) * 1e-3) / 1e9
+    for key, nt in (("hbm_read_gb_per_s", 0), ("hbm_read_nontemporal_gb_per_s", 1)):
+        idx = []
+        for _ in range(6):
+            e = t.start()
+            rc = lib.star_calib_hbm_read(vp(src.data_ptr()), nbytes, nt, vp(out.data_ptr()), stream)
+            idx.append(t.stop(e))
+            assert rc == 0
+        torch.cuda.synchronize()
+        res[key] = nbytes / (min(t.ms(i) for i in idx[1:]) * 1e-3) / 1e9
     res["hbm_read_bytes"] = nbytes
     res["note"] = ("calibration kernels (csrc/calib.hip): v_mfma_f32_16x16x32_bf16 only, 8 wavefronts per CU, "
-                   f"{iters} x 8 per wavefront per launch; grid-stride read of a copy of the K and V caches, best of 5")
+                   f"{iters} x 8 per wavefront per launch; grid-stride read of a copy of the K and V caches with ordinary and with non-temporal loads, best of 5 each")
     return res
 
 
@@ -645,7 +646,8 @@ def main():
         try:       # calibration only: its absence must not cost the run its result
             c = ceilings(bufs)
             out["roofline"]["frac_of_measured_mfma_rate"] = p1_tflops / c["mfma_random_operands_tflops"]
-            out["roofline_decode"]["frac_of_measured_hbm_read"] = dec_gbs / c["hbm_read_gb_per_s"]
+            out["roofline_decode"]["frac_of_measured_hbm_read"] = dec_gbs / max(
+                c["hbm_read_gb_per_s"], c["hbm_read_nontemporal_gb_per_s"])
         except (OSError, AssertionError) as exc:
             c = {"error": str(exc)}
         out["ceilings"] = c

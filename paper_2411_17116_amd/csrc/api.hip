@@ -41,13 +41,12 @@ static Geom make_geom(const star_attn_shape* s) {
 static int64_t ceil_div(int64_t x, int64_t y) { return (x + y - 1) / y; }
 static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
 
-// Workgroups of the decode kernel that are resident at once on an MI355X:
-// 256 CUs x 4 (one single-wavefront workgroup per SIMD; its 32 KiB LDS ring
-// allows that many per CU).
-#ifndef STAR_DECODE_WGS_PER_CU
-#define STAR_DECODE_WGS_PER_CU 4
-#endif
-constexpr int64_t DECODE_SLOTS = 256 * STAR_DECODE_WGS_PER_CU;
+// Workgroups of the decode kernel that are resident at once on an MI355X
+// (256 CUs): one split each under a flat plan.
+static int64_t decode_slots(const Geom& g, int64_t total) {
+  return 256 * (int64_t)decode_workgroups_per_cu(decode_cache_resident(g, total));
+}
+constexpr int64_t DECODE_SLOTS_MAX = 256 * 4;
 
 // Split plan for a phase-2 call with q_len new tokens that can see `total`
 // cache rows.  Decode-sized calls (G * q_len rows fit one 16-column MFMA tile)
@@ -69,7 +68,8 @@ static bool make_plan(const star_attn_shape* s, int64_t q_len, int64_t total, bo
   int64_t split_len;
   if (p->decode && !want_parts) {
     int64_t pairs = (int64_t)g.B * g.Hkv;
-    int64_t s0 = DECODE_SLOTS / pairs > 1 ? DECODE_SLOTS / pairs : 1;
+    int64_t slots = decode_slots(g, total);
+    int64_t s0 = slots / pairs > 1 ? slots / pairs : 1;
     split_len = round_up(ceil_div(total, s0), 32);
     if (split_len < 64) split_len = 64;
     p->flat = 1;
@@ -163,7 +163,7 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
       if (!make_plan(shape, q, shape->cache_capacity, parts != 0, &p)) continue;
       if (p.flat) {   // a shorter cache may need one split more than the full one; bound it
         int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
-        int64_t s0 = DECODE_SLOTS / pairs > 1 ? DECODE_SLOTS / pairs : 1;
+        int64_t s0 = DECODE_SLOTS_MAX / pairs > 1 ? DECODE_SLOTS_MAX / pairs : 1;
         if (p.s_total < s0) p.s_total = (int32_t)s0;
       }
       size_t b = plan_bytes(shape, p, q);

@@ -7,7 +7,8 @@
 //     depends on how much the operand bits toggle (constant operands run near
 //     the nominal peak, random ones well below).
 //   * star_calib_hbm_read: a grid-stride read of a buffer, 16 bytes per lane,
-//     the ceiling for a kernel that streams the KV cache once.
+//     with ordinary or non-temporal loads: the ceiling for a kernel that streams
+//     the KV cache once.
 // Both enqueue one kernel on the given stream; the caller times it.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -45,11 +46,13 @@ __global__ __launch_bounds__(CALIB_THREADS) void mfma_kernel(const u32x4* __rest
   out[blockIdx.x * CALIB_THREADS + threadIdx.x] = s;
 }
 
+template <bool NT>
 __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src, size_t n_vec,
                                                    unsigned* __restrict__ out) {
   u32x4 acc = {0u, 0u, 0u, 0u};
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) acc ^= src[i];
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
+    acc ^= NT ? __builtin_nontemporal_load(src + i) : src[i];
   out[blockIdx.x * blockDim.x + threadIdx.x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
 }
 
@@ -79,10 +82,12 @@ int star_calib_mfma(const void* seed, void* out, int iters, void* hip_stream) {
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 
-int star_calib_hbm_read(const void* src, size_t bytes, void* out, void* hip_stream) {
+// nontemporal != 0: the loads carry the non-temporal hint (data used once).
+int star_calib_hbm_read(const void* src, size_t bytes, int nontemporal, void* out, void* hip_stream) {
   if (!src || !out || bytes < 16 || ((uintptr_t)src & 15u)) return -1;
-  read_kernel<<<READ_WGS, 256, 0, (hipStream_t)hip_stream>>>((const u32x4*)src, bytes / 16,
-                                                             (unsigned*)out);
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (nontemporal) read_kernel<true><<<READ_WGS, 256, 0, st>>>((const u32x4*)src, bytes / 16, (unsigned*)out);
+  else read_kernel<false><<<READ_WGS, 256, 0, st>>>((const u32x4*)src, bytes / 16, (unsigned*)out);
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 

@@ -10,20 +10,23 @@
 //     s, s + S, s + 2S, ... so that at any moment the S wavefronts of a KV head
 //     read one contiguous window of its cache (every memory channel busy, none
 //     hot); with per-part outputs a split is a contiguous run inside one part;
-//   * the wavefront DMAs 32-key steps of K and V (8 KiB each) straight into a
-//     two-step LDS ring with global_load_lds_dwordx4 -- fully coalesced 1 KiB
-//     bursts, no VGPRs held by data in flight -- and waits with partial vmcnt so
-//     that one step (16 KiB) is in flight while one is consumed; 32 KiB of LDS
-//     per workgroup lets four of them share a CU, one per SIMD (measured: four
-//     wavefronts with one step ahead each stream 2 % faster than two with three
-//     ahead, one wavefront per CU 15 % slower);
+//   * a batch of NS steps is loaded into registers with plain 16-byte loads and
+//     then consumed in order -- K (8 KiB a step) straight in the layout the MFMA
+//     wants: lane (i, j4) takes key i, bytes 64t + 16 j4 .. +15 of its row for
+//     t = 0..3; V (8 KiB a step) as 1 KiB-contiguous bursts.  All waits are the
+//     compiler's (straight-line code, static register indices); while one
+//     wavefront computes, the other wavefronts of the CU keep the stream going;
+//   * a cache too large to stay in the 256 MB last-level cache between steps is
+//     read with non-temporal loads (every byte is used once: leaving it out of
+//     the caches is worth 9-16 % of the step at 0.5-4 GB); a smaller one with
+//     ordinary loads, so that the next step finds it there;
 //   * all G query heads of the KV group (and up to 16/G new tokens) form the 16
 //     columns of v_mfma_f32_16x16x32_bf16, so K and V are read once per KV head;
 //     S^T = K Q^T leaves each lane with keys of one query column, and the
-//     exponentiated tile is directly the B operand of O^T += V^T P^T, with V^T
-//     fragments from the LDS transposing read;
-//   * 16-byte chunks of a key row are rotated-XOR swizzled in LDS so both operand
-//     reads are conflict-free;
+//     exponentiated tile is directly the B operand of O^T += V^T P^T; V goes
+//     through a small LDS buffer (two 8 KiB halves used alternately) only to be
+//     read back transposed, 16-byte chunks rotated-XOR swizzled so that writes
+//     and transposing reads are conflict-free;
 //   * rows at or beyond cache_len are the new tokens: they are read from the
 //     call's Kq/Vq and written to the cache by the workgroup whose split holds
 //     them, so no separate append kernel runs before a decode step.
@@ -45,10 +48,6 @@ constexpr int D = 128;
 constexpr int ROWB = D * 2;
 constexpr int STEP = 32;                 // keys per pipeline step
 constexpr int STEPB = STEP * ROWB;       // 8 KiB of K (and of V) per step
-#ifndef STAR_DECODE_RING
-#define STAR_DECODE_RING 2
-#endif
-constexpr int RING = STAR_DECODE_RING;   // steps in the LDS ring
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -56,17 +55,6 @@ constexpr float LN2 = 0.6931471805599453f;
 
 // chunk c of key row r sits in slot c ^ swz(r)
 __device__ __forceinline__ int swz(int r) { return ((r << 1) & 15) | ((r >> 3) & 1); }
-
-// 16-byte DMA global -> LDS (lane L lands at lds_base + 16 L), address = sbase + voff
-__device__ __forceinline__ void dma16(const char* sbase, unsigned voff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
-}
-// same with a full per-lane 64-bit address
-__device__ __forceinline__ void dma16_flat(const char* ptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(ptr), "s"(lds_base) : "memory");
-}
 
 __device__ __forceinline__ float xor16(float x) {
   return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401F));
@@ -81,9 +69,15 @@ __device__ __forceinline__ float xor32_sum(float x) {
 }
 
 struct DecState {
-  bf16x8 q[4];     // Q^T fragments: q[t] = Q[column lane%16][32*(lane/16) + 8t .. +7]
+  bf16x8 q[4];     // Q^T fragments: q[t] = Q[column lane%16][32t + 8*(lane/16) .. +7]
   f32x4 o[8];      // O^T: o[dt][v] = O[column][16dt + 4*(lane/16) + v]
   float m, l;
+};
+
+// One 32-key step in registers.
+struct StepRegs {
+  i32x4 k[8];      // k[4kt + t]: key 16kt + lane%16, bytes 64t + 16*(lane/16) .. +15 (MFMA A operand)
+  i32x4 v[8];      // v[it]: key 4it + lane/16, bytes 16*(lane%16) .. +15
 };
 
 // Where a split's rows come from: cache rows below `cache_len`, the call's new
@@ -97,50 +91,54 @@ struct Source {
   int new_stride;
 };
 
-// DMA one 32-key step of K and V into ring slot `slot`.  Instruction `it` moves
-// rows 4it..4it+3; lane L moves (row 4it + L/16, slot L%16).  Rows at or past
-// `hi` re-read the last valid row (they are masked in the score tile).
-__device__ __forceinline__ void issue_step(const Source& src, int key0, int hi, unsigned lds_slot,
-                                           int lane, const unsigned (&voff)[4]) {
-  const unsigned ldsK = lds_slot, ldsV = lds_slot + STEPB;
+// Load the step [key0, key0 + 32).  Rows at or past `hi` re-read the last valid
+// row (they are masked in the score tile).
+template <bool NT>
+__device__ __forceinline__ void load_step(StepRegs& r, const Source& src, int key0, int hi, int lane) {
+  const int col = lane & 15, j4 = lane >> 4;
   if (key0 + STEP <= hi && key0 + STEP <= src.cache_len) {   // whole step from the cache
-    const char* kb = src.Kb + (size_t)key0 * ROWB;
-    const char* vb = src.Vb + (size_t)key0 * ROWB;
+    const char* kp = src.Kb + (size_t)key0 * ROWB + col * ROWB + j4 * 16;
+    const char* vp = src.Vb + (size_t)key0 * ROWB + j4 * ROWB + col * 16;
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
-      dma16(kb + (it >> 2) * 16 * ROWB, voff[it & 3], ldsK + it * 1024);
-      dma16(vb + (it >> 2) * 16 * ROWB, voff[it & 3], ldsV + it * 1024);
+      const i32x4* ka = (const i32x4*)(kp + (it >> 2) * 16 * ROWB + (it & 3) * 64);
+      const i32x4* va = (const i32x4*)(vp + it * 4 * ROWB);
+      r.k[it] = NT ? __builtin_nontemporal_load(ka) : *ka;
+      r.v[it] = NT ? __builtin_nontemporal_load(va) : *va;
     }
   } else {
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
-      int key = key0 + 4 * it + (lane >> 4);
-      key = key < hi ? key : hi - 1;
-      unsigned coff = voff[it & 3] & 255;
-      size_t off = key < src.cache_len ? (size_t)key * ROWB
-                                       : (size_t)(key - src.cache_len) * src.new_stride;
-      const char* kp = (key < src.cache_len ? src.Kb : src.Kn) + off + coff;
-      const char* vp = (key < src.cache_len ? src.Vb : src.Vn) + off + coff;
-      dma16_flat(kp, ldsK + it * 1024);
-      dma16_flat(vp, ldsV + it * 1024);
+      int kk = key0 + 16 * (it >> 2) + col;
+      kk = kk < hi ? kk : hi - 1;
+      const char* kp = kk < src.cache_len ? src.Kb + (size_t)kk * ROWB
+                                          : src.Kn + (size_t)(kk - src.cache_len) * src.new_stride;
+      r.k[it] = *(const i32x4*)(kp + (it & 3) * 64 + j4 * 16);
+      int vk = key0 + 4 * it + j4;
+      vk = vk < hi ? vk : hi - 1;
+      const char* vp = vk < src.cache_len ? src.Vb + (size_t)vk * ROWB
+                                          : src.Vn + (size_t)(vk - src.cache_len) * src.new_stride;
+      r.v[it] = *(const i32x4*)(vp + col * 16);
     }
   }
 }
 
-template <int SLOT>
-__device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr)[4],
-                                             const unsigned (&vaddr)[8], int key0, int lim,
-                                             bool masked, float c, int j4) {
-  constexpr int KOFF = SLOT * 2 * STEPB, VOFF = KOFF + STEPB;
+// VOFF (0 or STEPB) selects the LDS half this step's V goes through.
+__device__ __forceinline__ void compute_step(const int VOFF, DecState& w, const StepRegs& r,
+                                             const unsigned (&vw)[4], const unsigned (&vaddr)[8],
+                                             int key0, int lim, bool masked, float c, int j4) {
+  // V rows into LDS (row 4it + lane/16, swizzled chunk lane%16)
+#pragma unroll
+  for (int it = 0; it < 8; ++it)
+    *(LDS_AS i32x4*)(size_t)(vw[it & 3] + VOFF + (it >> 2) * 16 * ROWB) = r.v[it];
   f32x4 s[2];
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
     s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      bf16x8 a = *(LDS_AS bf16x8*)(size_t)(kaddr[t] + KOFF + kt * 16 * ROWB);
-      s[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, w.q[t], s[kt], 0, 0, 0);
-    }
+    for (int t = 0; t < 4; ++t)
+      s[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[4 * kt + t]),
+                                                      w.q[t], s[kt], 0, 0, 0);
   }
   if (masked) {
     int x = lim - key0 - 4 * j4;     // element (kt, v) is key key0 + 16kt + 4*j4 + v
@@ -187,18 +185,11 @@ __device__ __forceinline__ void compute_step(DecState& w, const unsigned (&kaddr
   }
 }
 
-// Wait until at most `pending` of the most recently issued steps are in flight
-// (16 DMA instructions per step).
-__device__ __forceinline__ void wait_steps(int pending) {
-  if (pending >= 3) asm volatile("s_waitcnt vmcnt(48)" ::: "memory");
-  else if (pending == 2) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
-  else if (pending == 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-
-// grid: x = split, y = kv head, z = batch; 64 threads
+// grid: x = split, y = kv head, z = batch; 64 threads.  NS = steps per batch of
+// loads, NT = non-temporal loads.
+template <int NS, bool NT>
 __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
-  __shared__ __attribute__((aligned(1024))) char lds[RING * 2 * STEPB];
+  __shared__ __attribute__((aligned(1024))) char lds[2 * STEPB];
   const Geom& g = a.g;
   const int lane = threadIdx.x;
   const int qc = lane & 15, j4 = lane >> 4;
@@ -252,19 +243,18 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
       *(i32x4*)(const_cast<char*>(src.Kb) + dof) = *(const i32x4*)(src.Kn + so);
       *(i32x4*)(const_cast<char*>(src.Vb) + dof) = *(const i32x4*)(src.Vn + so);
     }
-
-    // the stores are complete before DMAs are counted
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
-  // The query loads are issued here and consumed after the first step's wait:
-  // their latency overlaps the first DMAs instead of preceding them.
   DecState w;
   {
     const char* qrow = (const char*)a.Qq + (((size_t)beta * a.q_len + (live ? j : 0)) * g.Hq +
                                             (live ? head : kvh * g.G)) * ROWB;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) w.q[t] = *(const bf16x8*)(qrow + (32 * j4 + 8 * t) * 2);
+    for (int t = 0; t < 4; ++t) {
+      bf16x8 v = *(const bf16x8*)(qrow + (32 * t + 8 * j4) * 2);
+      if (!live) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};     // dead columns contribute zeros
+      w.q[t] = v;
+    }
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) w.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     w.m = -INFINITY;
@@ -272,12 +262,13 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   }
 
   const unsigned lds0 = (unsigned)(size_t)(LDS_AS char*)lds;
-  // K operand: in MFMA step t, lane (i = lane%16, j4) reads row i, chunk 4 j4 + t
-  // (Q uses the same assignment of d-chunks; the transposed one, 4t + j4, costs
-  // LDS bank conflicts on these 16-byte reads)
-  unsigned kaddr[4];
+  // V rows into LDS: lane writes row 4it + lane/16, chunk lane%16 (swizzled)
+  unsigned vw[4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) kaddr[t] = lds0 + qc * ROWB + (((4 * j4 + t) ^ swz(qc)) << 4);
+  for (int it = 0; it < 4; ++it) {
+    int row = 4 * it + j4;
+    vw[it] = lds0 + row * ROWB + ((qc ^ swz(row)) << 4);
+  }
   // V^T operand: source lane addresses row 4*j4 + (lane%16)/4 (+16 for the second
   // read), columns 16dt + 4*(lane%4) .. +3
   unsigned vaddr[8];
@@ -287,11 +278,6 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
     for (int dt = 0; dt < 8; ++dt)
       vaddr[dt] = lds0 + rr * ROWB + (((2 * dt + ((lane & 3) >> 1)) ^ swz(rr)) << 4) + 8 * (lane & 1);
   }
-  // DMA lane offsets: row (4it + lane/16) of a 16-row group, swizzled chunk
-  unsigned voff[4];
-#pragma unroll
-  for (int it = 0; it < 4; ++it)
-    voff[it] = (4 * it + (lane >> 4)) * ROWB + (((lane & 15) ^ swz(4 * it + (lane >> 4))) << 4);
 
   const float c = g.scale * LOG2E;
   // keys below free_hi (what the call's first token sees) are visible to every
@@ -301,39 +287,21 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
   const int first_lim = (int)visible_limit(a, 0);
   const int free_hi = first_lim < hi ? first_lim : hi;
 
-  // ring slot of step s is s % RING; AHEAD = RING - 1 steps are in flight while
-  // one is consumed
-  constexpr int AHEAD = RING - 1;
-  static_assert(RING >= 2 && RING <= 4, "vmcnt holds at most 63 outstanding DMAs");
+  // NS steps are loaded into registers at once and then consumed in order; the
+  // other wavefronts of the CU stream while this one computes
+  for (int s = 0; s < nsteps; s += NS) {
+    StepRegs r[NS];
 #pragma unroll
-  for (int i = 0; i < AHEAD; ++i)
-    if (i < nsteps) issue_step(src, base + i * stride, hi, lds0 + i * 2 * STEPB, lane, voff);
-  for (int s = 0; s < nsteps; s += RING) {
+    for (int u = 0; u < NS; ++u) {
+      const int cur = s + u < nsteps ? s + u : nsteps - 1;     // past the end: re-read the last step
+      load_step<NT>(r[u], src, base + cur * stride, hi, lane);
+    }
 #pragma unroll
-    for (int u = 0; u < RING; ++u) {
-      const int cur = s + u;
-      if (cur >= nsteps) break;
-      const int key0 = base + cur * stride;
-      // the slot that held step cur-1 is free: every LDS read of it has returned
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (cur + AHEAD < nsteps)
-        issue_step(src, key0 + AHEAD * stride, hi, lds0 + ((u + AHEAD) % RING) * 2 * STEPB, lane, voff);
-      int later = nsteps - 1 - cur;
-      wait_steps(later < AHEAD ? later : AHEAD);
-      if (cur == 0) {
-        // first use of the query: the loads were issued before every DMA, so the
-        // wait above covers them; dead columns contribute zeros
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          asm volatile("" : "+v"(w.q[t]));
-          if (!live) w.q[t] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-        }
-      }
+    for (int u = 0; u < NS; ++u) {
+      if (s + u >= nsteps) break;
+      const int key0 = base + (s + u) * stride;
       const bool masked = key0 + STEP > free_hi;
-      if (u == 0) compute_step<0>(w, kaddr, vaddr, key0, lim, masked, c, j4);
-      else if (u == 1) compute_step<1>(w, kaddr, vaddr, key0, lim, masked, c, j4);
-      else if (u == 2) compute_step<2>(w, kaddr, vaddr, key0, lim, masked, c, j4);
-      else compute_step<3>(w, kaddr, vaddr, key0, lim, masked, c, j4);
+      compute_step((u & 1) * STEPB, w, r[u], vw, vaddr, key0, lim, masked, c, j4);
     }
   }
 
@@ -354,7 +322,9 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(Phase2Args a) {
 hipError_t launch_phase2_decode_bf16(const Phase2Args& a, hipStream_t st) {
   const Geom& g = a.g;
   if (g.Hkv > 65535 || g.B > 65535) return hipErrorInvalidValue;
-  decode_bf16_kernel<<<dim3((unsigned)a.plan.s_total, (unsigned)g.Hkv, (unsigned)g.B), 64, 0, st>>>(a);
+  const dim3 grid((unsigned)a.plan.s_total, (unsigned)g.Hkv, (unsigned)g.B);
+  if (decode_cache_resident(g, visible_total(a))) decode_bf16_kernel<1, false><<<grid, 64, 0, st>>>(a);
+  else decode_bf16_kernel<2, true><<<grid, 64, 0, st>>>(a);
   return hipGetLastError();
 }
 

@@ -116,6 +116,16 @@ struct MergeArgs {
   float* LSE;           // merged), and its log-sum-exp [B, Hq, q_len]; each may be null
 };
 
+// The streaming decode kernel runs in two set-ups.  K and V of a call that fit
+// the 256 MB last-level cache with room to spare are found there by the next
+// decode step: ordinary loads, one step per batch, four single-wavefront
+// workgroups per CU.  Larger ones are used once per step and gone before the
+// next: non-temporal loads, two steps per batch (256 registers), three per CU.
+__host__ __device__ inline bool decode_cache_resident(const Geom& g, int64_t total_keys) {
+  return 2 * (int64_t)g.B * g.Hkv * total_keys * g.d * 2 <= ((int64_t)192 << 20);
+}
+inline int decode_workgroups_per_cu(bool resident) { return resident ? 4 : 3; }
+
 // Key range [lo, hi) of split s of a plan that is not flat (hi clipped to what
 // exists for this call).
 __host__ __device__ inline void split_range(const SplitPlan& p, int64_t L, int64_t b,
