@@ -49,20 +49,24 @@ __device__ __forceinline__ void attend_range(RowState<D>& st, const float* __res
     __syncthreads();
     for (int c0 = 0; c0 < TK; c0 += CH) {
       if (k0 + c0 >= hi) break;
-      float s[CH];
+      // two partial sums per logit, added at the end: chains of d/2 terms keep the
+      // rounding of a large logit (a planted pair reaches 25 in log2 units) down
+      float s[CH], s2[CH];
 #pragma unroll
-      for (int kk = 0; kk < CH; ++kk) s[kk] = 0.f;
+      for (int kk = 0; kk < CH; ++kk) s[kk] = s2[kk] = 0.f;
 #pragma unroll
       for (int dd = 0; dd < D; dd += 4) {
 #pragma unroll
         for (int kk = 0; kk < CH; ++kk) {
           f32x4 kv = *(const f32x4*)(Ks + (c0 + kk) * D + dd);
           s[kk] = __builtin_fmaf(st.q[dd], kv[0], s[kk]);
-          s[kk] = __builtin_fmaf(st.q[dd + 1], kv[1], s[kk]);
+          s2[kk] = __builtin_fmaf(st.q[dd + 1], kv[1], s2[kk]);
           s[kk] = __builtin_fmaf(st.q[dd + 2], kv[2], s[kk]);
-          s[kk] = __builtin_fmaf(st.q[dd + 3], kv[3], s[kk]);
+          s2[kk] = __builtin_fmaf(st.q[dd + 3], kv[3], s2[kk]);
         }
       }
+#pragma unroll
+      for (int kk = 0; kk < CH; ++kk) s[kk] += s2[kk];
       float cmax = -INFINITY;
 #pragma unroll
       for (int kk = 0; kk < CH; ++kk) {

@@ -22,6 +22,13 @@ import workloads
 from oracle import star_oracle as so
 
 TOL = {"fp32": dict(o=1e-5, lse=1e-5), "bf16": dict(o=2e-2, lse=1e-2)}
+# The fp32 bound on a log-sum-exp is 1e-5 for values up to 8 and grows in
+# proportion beyond: the statistic is dominated by its largest logit, a d-term
+# fp32 dot product whose rounding grows with its magnitude (a planted pair
+# gives a logit, and an LSE, near 17: one ulp is 1.9e-6 there, and 1e-5 would be
+# five ulps for the whole chain of d fused multiply-adds, the exponentials and
+# the logarithm).  bf16 results are compared against the plain 1e-2.
+LSE_MAGNITUDE_FLOOR = {"fp32": 8.0, "bf16": None}
 
 
 class LazyTensor:
@@ -120,13 +127,20 @@ def _maxabs(a: np.ndarray, b: np.ndarray) -> float:
     return float(d.max())
 
 
-def _lse_err(got: np.ndarray, want: np.ndarray) -> float:
-    """max |got - want| where -inf must match -inf exactly."""
+def _lse_err(got: np.ndarray, want: np.ndarray, dtype: str = "bf16") -> float:
+    """max |got - want| where -inf must match -inf exactly; with a magnitude
+    floor for the dtype, the difference is divided by max(1, |want| / floor)."""
     got = got.astype(np.float64)
+    want = np.asarray(want, np.float64)
     inf_w = np.isneginf(want)
     if (np.isneginf(got) != inf_w).any():
         return math.inf
-    return _maxabs(got[~inf_w], want[~inf_w])
+    g, w = got[~inf_w], want[~inf_w]
+    floor = LSE_MAGNITUDE_FLOOR[dtype]
+    if floor is None or g.size == 0:
+        return _maxabs(g, w)
+    d = np.abs(g - w) / np.maximum(1.0, np.abs(w) / floor)
+    return math.inf if np.isnan(d).any() else float(d.max())
 
 
 def check_phase1(run: HipRun, triples: Sequence, cache_heads: Optional[Sequence] = None
@@ -139,7 +153,7 @@ def check_phase1(run: HipRun, triples: Sequence, cache_heads: Optional[Sequence]
     bi, hi, ri = idx.unbind(1)
     O_got = run.O_ctx[bi, ri, hi].float().cpu().numpy()
     LSE_got = run.LSE_ctx[bi, hi, ri].cpu().numpy()
-    res = {"phase1_O": _maxabs(O_got, O_ref), "phase1_LSE": _lse_err(LSE_got, LSE_ref)}
+    res = {"phase1_O": _maxabs(O_got, O_ref), "phase1_LSE": _lse_err(LSE_got, LSE_ref, cfg.dtype)}
     # cache: every context token exactly once, bit-exact
     if cache_heads is None:
         cache_heads = [(beta, g) for beta in range(cfg.B) for g in range(cfg.Hkv)]
@@ -177,7 +191,7 @@ def check_phase2(run: HipRun, Qn: torch.Tensor, appended: Sequence[torch.Tensor]
         # an empty part carries no output; compare outputs where the part exists
         exists = ~np.isneginf(ref["LSE_part"])
         res[f"{tag}_O_part"] = _maxabs(Op[exists], ref["O_part"][exists])
-        res[f"{tag}_LSE_part"] = _lse_err(Lp, ref["LSE_part"])
+        res[f"{tag}_LSE_part"] = _lse_err(Lp, ref["LSE_part"], cfg.dtype)
     return res
 
 
