@@ -474,6 +474,24 @@ def ceilings(bufs):
             assert rc == 0
         torch.cuda.synchronize()
         res[f"mfma_{name}_operands_tflops"] = lib.star_calib_mfma_flops(iters) / (t.ms(idx[1]) * 1e-3) / 1e12
+    # MFMA and softmax-like VALU work on the two wavefronts of a SIMD: alone and together
+    lib.star_calib_coexec_cycle_words.restype = ctypes.c_size_t
+    lib.star_calib_coexec.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    cyc = torch.zeros(lib.star_calib_coexec_cycle_words(), dtype=torch.int64, device="cuda")
+    co_iters = 20000
+    co = {}
+    for mode, tag in ((1, "alone"), (2, "alone"), (3, "together")):
+        assert lib.star_calib_coexec(vp(out.data_ptr()), vp(cyc.data_ptr()), co_iters, mode, stream) == 0
+        torch.cuda.synchronize()
+        c = cyc.view(-1, 8).double()
+        if mode & 1:
+            co[f"clocks_per_mfma_{tag}"] = float(c[:, :4].mean()) / (8 * co_iters)
+        if mode & 2:
+            co[f"clocks_per_softmax_valu_group_{tag}"] = float(c[:, 4:].mean()) / co_iters
+    co["note"] = ("one wavefront per SIMD issues v_mfma_f32_16x16x32_bf16 only, its SIMD neighbour 9 v_fma_f32 + 4 "
+                  "v_exp_f32 per iteration (the VALU mix of the softmax of 8 MFMAs' worth of scores); shader clocks "
+                  "per MFMA and per VALU group, each stream alone and both together")
+    res["mfma_valu_coexecution"] = co
     src = torch.cat([bufs["Kc"].view(-1), bufs["Vc"].view(-1)])   # as many bytes as a decode step reads
     nbytes = src.numel() * src.element_size()
     for key, nt in (("hbm_read_gb_per_s", 0), ("hbm_read_nontemporal_gb_per_s", 1)):

@@ -9,7 +9,14 @@
 //   * star_calib_hbm_read: a grid-stride read of a buffer, 16 bytes per lane,
 //     with ordinary or non-temporal loads: the ceiling for a kernel that streams
 //     the KV cache once.
-// Both enqueue one kernel on the given stream; the caller times it.
+//   * star_calib_coexec: four wavefronts of a workgroup (one per SIMD) issue
+//     MFMAs only, the other four (their SIMD neighbours) the VALU mix of an
+//     attention softmax (9 multiply-adds and 4 exponentials per 8 MFMAs' worth of
+//     scores); each wavefront reports its own cycle count.  Run with either group
+//     alone and with both it shows how much of the two streams a SIMD executes at
+//     the same time.
+// All enqueue one kernel on the given stream; the caller times it (or reads the
+// cycle counts).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -58,6 +65,49 @@ __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src
 
 constexpr int READ_WGS = 256 * 8;
 
+// mode bit 0: wavefronts 0-3 run 8 independent MFMAs per iteration; bit 1:
+// wavefronts 4-7 run 9 fused multiply-adds and 4 exponentials per iteration.
+// cycles[8 * workgroup + wavefront] = shader clocks the wavefront's loop took.
+__global__ __launch_bounds__(CALIB_THREADS) void coexec_kernel(float* __restrict__ out,
+                                                               long long* __restrict__ cycles,
+                                                               int iters, int mode, float seed) {
+  const int wave = threadIdx.x >> 6;
+  const long long t0 = clock64();
+  float r = 0.f;
+  if (wave < 4 && (mode & 1)) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[i] = (__bf16)(seed + i + threadIdx.x);
+      b[i] = (__bf16)(seed * i - threadIdx.x);
+    }
+    f32x4 c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) c[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r += c[i][0] + c[i][1] + c[i][2] + c[i][3];
+  } else if (wave >= 4 && (mode & 2)) {
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = seed * (i + 1) + threadIdx.x * 1e-3f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) x[u & 7] = __builtin_fmaf(x[u & 7], 0.999f, 0.001f);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) x[u] = __builtin_amdgcn_exp2f(x[u]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r += x[i];
+  }
+  const long long t1 = clock64();
+  out[blockIdx.x * CALIB_THREADS + threadIdx.x] = r;
+  if ((threadIdx.x & 63) == 0) cycles[blockIdx.x * 8 + wave] = t1 - t0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -83,6 +133,16 @@ int star_calib_mfma(const void* seed, void* out, int iters, void* hip_stream) {
 }
 
 // nontemporal != 0: the loads carry the non-temporal hint (data used once).
+// cycles: CALIB_WGS * 8 int64 (device).  mode: 1 = MFMA wavefronts only, 2 = VALU
+// wavefronts only, 3 = both.
+size_t star_calib_coexec_cycle_words(void) { return (size_t)CALIB_WGS * 8; }
+int star_calib_coexec(void* out, void* cycles, int iters, int mode, void* hip_stream) {
+  if (!out || !cycles || iters <= 0 || mode < 1 || mode > 3) return -1;
+  coexec_kernel<<<CALIB_WGS, CALIB_THREADS, 0, (hipStream_t)hip_stream>>>(
+      (float*)out, (long long*)cycles, iters, mode, 0.5f);
+  return hipGetLastError() == hipSuccess ? 0 : -2;
+}
+
 int star_calib_hbm_read(const void* src, size_t bytes, int nontemporal, void* out, void* hip_stream) {
   if (!src || !out || bytes < 16 || ((uintptr_t)src & 15u)) return -1;
   hipStream_t st = (hipStream_t)hip_stream;
