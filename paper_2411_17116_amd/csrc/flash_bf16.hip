@@ -32,10 +32,15 @@
 //     touches LDS.
 //   * Softmax runs in the log2 domain in fp32 against a reference maximum taken
 //     from the row's first 32 keys: the common path is one fma + one exp per
-//     score, a packed bf16 conversion and a dot2 for the row sum, with no
-//     maximum search and no rescale (O / l does not depend on the reference).
-//     If a row sum shows that the reference was too low to be safe, the
-//     workgroup redoes its rows with the exact online softmax.
+//     score and a packed bf16 conversion, with no maximum search and no rescale
+//     (O / l does not depend on the reference).  The row sums come out of the
+//     matrix pipe as well: one more MFMA per row block and unit multiplies P^T by
+//     an operand whose first row is all ones, which leaves the sums of the bf16
+//     numerators in row 0 of an accumulator (13 VALU instructions fewer per 32
+//     MFMAs than summing on the VALU; what bounds this kernel is the number of
+//     instructions a wavefront issues).  If a row sum shows that the reference
+//     was too low to be safe, the workgroup redoes its rows with the exact
+//     online softmax.
 //   * The key loop is software-pipelined per 32-key unit: the QK MFMAs of unit
 //     u+1, the exponentials of unit u and the PV MFMAs of unit u-1 share one
 //     scheduling region whose order is pinned with sched_group_barrier.
@@ -157,7 +162,10 @@ struct WaveState {
   float m[RB];        // reference maximum of the raw logits (uniform over a row's four lanes)
   float neg_mc[RB];   // -m * c (0 while m == -inf)
   float l[RB];        // this lane's share of the running sum of 2^((s-m) c)
-  float lmax;         // largest per-unit partial row sum seen by the fast loop
+  float lmax;         // fast loop: largest row sum of the wavefront's rows (safe-range check)
+  f32x4 lacc[RB];     // fast loop: row sums accumulated by MFMA; row 0 of ones * P^T, i.e.
+                      // element 0 of the lanes with j4 == 0 holds the sum of the lane's row
+  bf16x8 ones;        // that MFMA's A operand: row 0 all ones, the other rows zero
 };
 
 // Per-lane LDS addresses and DMA offsets, fixed for the whole kernel.
@@ -200,10 +208,10 @@ struct Scores {
 
 // The fast key loop keeps ONE reference maximum per row, taken from the row's
 // first 32 keys, and never rescales: p = 2^(s c - m c) against any fixed m gives
-// the same O / l.  It only has to stay finite, so the loop tracks the largest
-// per-unit row sum and, if one exceeds this limit (a score more than ~40 nats
-// above the reference), the workgroup redoes its rows with the exact online
-// softmax (SAFE mode), which searches the maximum of every unit.
+// the same O / l.  It only has to stay finite, so the row sums are checked when
+// the loop ends and, if one exceeds this limit (a score more than ~40 nats above
+// the reference), the workgroup redoes its rows with the exact online softmax
+// (SAFE mode), which searches the maximum of every unit.
 constexpr float LSUM_LIMIT = 1.152921504606846976e18f;   // 2^60
 
 __device__ __forceinline__ float unit_max(const Scores& x) {
@@ -231,6 +239,15 @@ __device__ __forceinline__ float softmax_unit(const Scores& x, float neg_mc, bf1
       lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
     }
   return lsum;
+}
+
+// The same numerators without the row sum (the fast loop sums them with an MFMA).
+__device__ __forceinline__ void softmax_unit_p(const Scores& x, float neg_mc, bf16x8& p, float c) {
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      p[4 * kt + v] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(x.s[kt][v], c, neg_mc));
 }
 
 // Raise the reference of row block rb to the maximum seen so far; returns the
@@ -306,8 +323,9 @@ __device__ __forceinline__ bf16x8 read_v(const LaneAddr& la, int dt, int off) {
 
 // One pipeline stage holds three independent pieces of work:
 //   QK  : s_next  = K[unit u+1] Q^T          (8 RB MFMAs, K fragments from LDS at KOFF)
-//   SM  : p_cur   = softmax numerators of s_cur (unit u), updates w.l / w.lmax
-//   PV  : O^T    += V[unit u-1]^T p_prev      (8 RB MFMAs, V^T fragments from LDS at VOFF)
+//   SM  : p_cur   = softmax numerators of s_cur (unit u)  (SAFE: also w.l, w.m)
+//   PV  : O^T    += V[unit u-1]^T p_prev      (8 RB MFMAs, V^T fragments from LDS at VOFF;
+//                  fast loop: RB more for the row sums)
 // so that the MFMAs of two units hide the exponentials of the third.  The
 // sched_group_barrier sequence at the end pins the instruction order inside the
 // stage: operand fragments are read from LDS two fragment pairs ahead of their
@@ -353,9 +371,7 @@ __device__ __forceinline__ void stage(WaveState& w, const LaneAddr& la, Scores (
         alpha[rb] = raise_reference(w, rb, s_cur[rb], c);
         w.l[rb] = __builtin_fmaf(w.l[rb], alpha[rb], softmax_unit(s_cur[rb], w.neg_mc[rb], p_cur[rb], c));
       } else {
-        float lsum = softmax_unit(s_cur[rb], w.neg_mc[rb], p_cur[rb], c);
-        w.l[rb] += lsum;
-        w.lmax = fmaxf(w.lmax, lsum);
+        softmax_unit_p(s_cur[rb], w.neg_mc[rb], p_cur[rb], c);
       }
     }
   }
@@ -376,6 +392,11 @@ __device__ __forceinline__ void stage(WaveState& w, const LaneAddr& la, Scores (
         w.o[rb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[i], p_prev[rb], w.o[rb][i], 0, 0, 0);
     }
   }
+  if (PV && !SAFE) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      w.lacc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.ones, p_prev[rb], w.lacc[rb], 0, 0, 0);
+  }
   if (QK && SM && PV) {
     if (!PRE_IN) __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
 #pragma unroll
@@ -383,18 +404,22 @@ __device__ __forceinline__ void stage(WaveState& w, const LaneAddr& la, Scores (
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if (i < 6 || PRE_OUT) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
       __builtin_amdgcn_sched_group_barrier(0x002, SAFE ? 3 : 2, 0);
     }
+    if (!SAFE) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
   }
   if (SM) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(w.l[rb]), "+v"(p_cur[rb]));
-    asm volatile("" : "+v"(w.lmax));
   }
   __builtin_amdgcn_sched_barrier(0);
 }
@@ -480,7 +505,8 @@ __device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     raise_reference(w, rb, r.sA[rb], c);
-    w.l[rb] = softmax_unit(r.sA[rb], w.neg_mc[rb], r.pA[rb], c);
+    if (SAFE) w.l[rb] = softmax_unit(r.sA[rb], w.neg_mc[rb], r.pA[rb], c);
+    else softmax_unit_p(r.sA[rb], w.neg_mc[rb], r.pA[rb], c);
   }
 
   // Tile t: V tile t is consumed while K tile t+1 produces the next scores.
@@ -507,6 +533,7 @@ __device__ __forceinline__ void reset_state(WaveState& w) {
     w.m[rb] = -INFINITY;
     w.neg_mc[rb] = 0.f;
     w.l[rb] = 0.f;
+    w.lacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
   w.lmax = 0.f;
 }
@@ -546,7 +573,18 @@ __device__ __forceinline__ void attend(WaveState& w, const TileSeq& seq, const i
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(w.q[rb][t]));
+  {
+    const __bf16 o = (la.tid & 15) == 0 ? (__bf16)1.0f : (__bf16)0.0f;
+    w.ones = bf16x8{o, o, o, o, o, o, o, o};
+  }
   key_loop<false>(w, la, seq, row_lim, wave_lo, c, lds0);
+  // row 0 of the ones-row product sits in element 0 of the lanes with j4 == 0: the row's whole sum
+  // (quad_sum over the row's four lanes then finds it once); sums that left the safe range show here
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    w.l[rb] = la.j4 == 0 ? w.lacc[rb][0] : 0.f;
+    w.lmax = fmaxf(w.lmax, w.l[rb]);
+  }
 
   // Did any row of any wavefront leave the safe range?  One LDS word per
   // wavefront; __syncthreads() (fence + barrier) orders the tile reads before the
