@@ -419,7 +419,10 @@ __device__ __forceinline__ void stage(WaveState& w, const LaneAddr& la, Scores (
   }
   if (SM) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(w.l[rb]), "+v"(p_cur[rb]));
+    for (int rb = 0; rb < RB; ++rb) {
+      if (SAFE) asm volatile("" : "+v"(w.l[rb]), "+v"(p_cur[rb]));
+      else asm volatile("" : "+v"(p_cur[rb]));
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
 }
