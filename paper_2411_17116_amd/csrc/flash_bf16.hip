@@ -457,13 +457,17 @@ __device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, cons
     int nk0, nhi;
     seq.tile(t + 1, &nk0, &nhi);
     issue_tile(seq.vbase(t + 1), seq.stride(t + 1), nk0, nhi, lds0 + VF, la);
+    // one wave-uniform test per tile: does any of its keys need a mask for this wavefront?
+    const bool anchor_tile = t + 1 < seq.n_a;
+    const int mask_from = anchor_tile ? nhi : (wave_lo < nhi ? wave_lo : nhi);
+    const bool need_mask = nk0 + TKEYS > mask_from;
     stage<SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB, r.pA,
                                                                        c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    mask_if_needed(r.sA, nk0, nhi, wave_lo, row_lim, la.j4, t + 1 < seq.n_a);
+    if (need_mask) mask_if_needed(r.sA, nk0, nhi, wave_lo, row_lim, la.j4, anchor_tile);
     stage<SAFE, true, true, true, KN + H, VC + H, true>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
-    mask_if_needed(r.sB, nk0 + 32, nhi, wave_lo, row_lim, la.j4, t + 1 < seq.n_a);
+    if (need_mask) mask_if_needed(r.sB, nk0 + 32, nhi, wave_lo, row_lim, la.j4, anchor_tile);
   } else {
     stage<SAFE, false, true, true, 0, VC>(w, la, r.sA, r.sB, r.pB, r.pA, c, alpha, pre);
     if (SAFE) rescale(w, alpha);
