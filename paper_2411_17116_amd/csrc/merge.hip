@@ -22,12 +22,25 @@
 // eight round trips); a query-encode call has thousands of rows and a few splits per
 // part (8 groups x 4).  Traffic is s_total * (d + 1) floats per row
 // -- negligible next to the cache.
+//
+// The fold over parts keeps a compensation term per accumulator (Kahan
+// summation): a context cut into hundreds of small blocks is hundreds of
+// sequential additions, and in fp32 their rounding errors would otherwise add up
+// to the 1e-5 the fp32 path is held to.
 #include "star_internal.h"
 
 namespace star {
 
 namespace {
 
+
+// sum += x with the rounding error of the addition carried in `comp`
+__device__ __forceinline__ void add_compensated(float& sum, float& comp, float x) {
+  const float y = x - comp;
+  const float t = sum + y;
+  comp = (t - sum) - y;
+  sum = t;
+}
 
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
   unsigned int u = __float_as_uint(f);
@@ -53,10 +66,10 @@ __global__ __launch_bounds__(32 * GROUPS) void merge_kernel(MergeArgs a) {
   const int64_t base = (int64_t)beta * a.batch_stride + (int64_t)h * a.q_len + j;   // split 0
   const int n_parts = p.flat ? 1 : p.n_blocks + 1;
 
-  float m_g = -INFINITY, l_g = 0.f;
-  float acc_g[E];
+  float m_g = -INFINITY, l_g = 0.f, l_c = 0.f;
+  float acc_g[E], acc_c[E];
 #pragma unroll
-  for (int e = 0; e < E; ++e) acc_g[e] = 0.f;
+  for (int e = 0; e < E; ++e) acc_g[e] = acc_c[e] = 0.f;
 
   for (int m = 0; m < n_parts; ++m) {
     int s_lo, s_hi;
@@ -135,9 +148,15 @@ __global__ __launch_bounds__(32 * GROUPS) void merge_kernel(MergeArgs a) {
         float m_new = fmaxf(m_g, lse_m);
         float sc_old = expf(m_g - m_new);     // 0 on the first non-empty part
         float sc_new = expf(lse_m - m_new);
+        if (sc_old != 1.f) {                  // the maximum moved: rescale sums and compensations
 #pragma unroll
-        for (int e = 0; e < E; ++e) acc_g[e] = acc_g[e] * sc_old + sc_new * A_m[e];
-        l_g = l_g * sc_old + sc_new;
+          for (int e = 0; e < E; ++e) { acc_g[e] *= sc_old; acc_c[e] *= sc_old; }
+          l_g *= sc_old;
+          l_c *= sc_old;
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) add_compensated(acc_g[e], acc_c[e], sc_new * A_m[e]);
+        add_compensated(l_g, l_c, sc_new);
         m_g = m_new;
       }
     }
@@ -176,10 +195,10 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a, int64_t n_
   const int64_t base = (int64_t)beta * a.batch_stride + (int64_t)h * a.q_len + j;
   const int n_parts = p.flat ? 1 : p.n_blocks + 1;
 
-  float m_g = -INFINITY, l_g = 0.f;
-  float acc_g[E];
+  float m_g = -INFINITY, l_g = 0.f, l_c = 0.f;
+  float acc_g[E], acc_c[E];
 #pragma unroll
-  for (int e = 0; e < E; ++e) acc_g[e] = 0.f;
+  for (int e = 0; e < E; ++e) acc_g[e] = acc_c[e] = 0.f;
   for (int m = 0; m < n_parts; ++m) {
     int s_lo, s_hi;
     if (p.flat) { s_lo = 0; s_hi = p.s_total; }
@@ -229,9 +248,15 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a, int64_t n_
       float m_new = fmaxf(m_g, lse_m);
       float sc_old = expf(m_g - m_new);          // 0 on the first non-empty part
       float sc_new = expf(lse_m - m_new);
+      if (sc_old != 1.f) {                       // the maximum moved: rescale sums and compensations
 #pragma unroll
-      for (int e = 0; e < E; ++e) acc_g[e] = acc_g[e] * sc_old + sc_new * A_m[e];
-      l_g = l_g * sc_old + sc_new;
+        for (int e = 0; e < E; ++e) { acc_g[e] *= sc_old; acc_c[e] *= sc_old; }
+        l_g *= sc_old;
+        l_c *= sc_old;
+      }
+#pragma unroll
+      for (int e = 0; e < E; ++e) add_compensated(acc_g[e], acc_c[e], sc_new * A_m[e]);
+      add_compensated(l_g, l_c, sc_new);
       m_g = m_new;
     }
   }

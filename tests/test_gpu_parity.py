@@ -37,6 +37,16 @@ def test_fp32_head_dim_128():
     _report(ph.run_parity(cfg, all_rows=True))
 
 
+def test_fp32_hundreds_of_one_token_blocks():
+    """Block size 1 without an anchor: 513 context parts of one token each, so
+    the merge of a query row is 514 sequential additions per accumulator -- the
+    case that needs the compensated part fold to stay within the fp32
+    tolerance (an uncompensated fp32 fold of these pairs is off by ~1e-5)."""
+    cfg = workloads.StarConfig("f32b1", "fp32", 1, 4, 1, 128, 513, 1, 0, 70, 3, seed=5200023,
+                               n_planted=2)
+    _report(ph.run_parity(cfg, all_rows=True))
+
+
 @pytest.mark.parametrize("Hq,Hkv,L,b,a,lq,nd", [
     (4, 1, 2048, 512, 512, 40, 3),     # G = 4: four heads per workgroup
     (8, 1, 1500, 400, 100, 130, 2),    # G = 8, ragged everything, anchor < block
