@@ -204,9 +204,10 @@ __global__ __launch_bounds__(ROWS) void phase2_f32_kernel(Phase2Args a, int row_
 
 hipError_t launch_phase1_f32(const Phase1Args& a, hipStream_t st) {
   const Geom& g = a.g;
-  int n = (int)((g.L + g.b - 1) / g.b);
+  int64_t n = (g.L + g.b - 1) / g.b;
   int64_t bmax = g.b < g.L ? g.b : g.L;
   int tpb = (int)((bmax + ROWS - 1) / ROWS);
+  if (n * tpb > 0x7fffffff) return hipErrorInvalidValue;
   dim3 grid((unsigned)(n * tpb), (unsigned)g.Hq, (unsigned)g.B);
   if (g.d == 64) phase1_f32_kernel<64><<<grid, ROWS, 0, st>>>(a, tpb);
   else phase1_f32_kernel<128><<<grid, ROWS, 0, st>>>(a, tpb);
@@ -216,6 +217,7 @@ hipError_t launch_phase1_f32(const Phase1Args& a, hipStream_t st) {
 hipError_t launch_phase2_f32(const Phase2Args& a, hipStream_t st) {
   const Geom& g = a.g;
   int row_tiles = (a.q_len + ROWS - 1) / ROWS;
+  if ((int64_t)g.B * a.plan.s_total * row_tiles > 0x7fffffff) return hipErrorInvalidValue;
   dim3 grid((unsigned)((int64_t)g.B * a.plan.s_total * row_tiles), (unsigned)g.Hq, 1);
   if (g.d == 64) phase2_f32_kernel<64><<<grid, ROWS, 0, st>>>(a, row_tiles);
   else phase2_f32_kernel<128><<<grid, ROWS, 0, st>>>(a, row_tiles);

@@ -277,6 +277,7 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a, int64_t n_
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st) {
   const int64_t rows = (int64_t)a.g.B * a.g.Hq * a.q_len;
+  if (rows > 0x7fffffff) return hipErrorInvalidValue;
   const SplitPlan& p = a.plan;
   // splits the largest part is made of
   const int per_part = p.flat ? p.s_total : (p.spb > p.st ? p.spb : p.st);
