@@ -46,7 +46,13 @@
 //     scheduling region whose order is pinned with sched_group_barrier.
 //   * Only tiles that touch a row's causal frontier or a ragged range end take
 //     the masking path.
+//   * Phase 1 is launched with one workgroup per CU; the workgroups draw their
+//     work items (a row tile of one block and KV head) from eight ticket queues,
+//     each XCD from its own first (one KV head per XCD's L2 when Hkv is a
+//     multiple of 8) and from the others once that is empty.
 #include "star_internal.h"
+
+#include <atomic>
 
 namespace star {
 
@@ -622,19 +628,44 @@ __device__ __forceinline__ void load_q(WaveState& w, int rb, const char* qrow, i
 // tokens (and their causal frontier) whenever the group has at least RB heads.
 
 // ------------------------------------------------------------------ phase 1
-// grid.x enumerates (kv head fastest, then work items); see launch_phase1_bf16.
-__global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1Args a, int hpw,
-                                                                          int tpb, int n_hs) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
+// Work items are numbered (kv head fastest, then the rest; see launch_phase1_bf16)
+// and dealt to eight queues, item v to queue v % 8 -- the XCD that workgroup v of
+// a plain launch would run on, so that with Hkv a multiple of 8 an XCD's L2 serves
+// one KV head.  The kernel is launched with one workgroup per CU; each takes the
+// next item of its XCD's queue until that is empty, then of the other queues: the
+// XCDs of one chip differ by a few per cent in clock under the power limit, and
+// with a fixed share each the launch would last as long as the slowest needs.
+// Launches take the ticket slots in turn (a launch's first kernel clears its
+// slot), so up to TICKET_SLOTS phase-1 launches of one process may be in flight
+// on a device at once.
+constexpr int TICKET_SLOTS = 64;
+__device__ unsigned int phase1_tickets[TICKET_SLOTS][8];
+
+__global__ void phase1_tickets_reset_kernel(int slot) {
+  if (threadIdx.x < 8) phase1_tickets[slot][threadIdx.x] = 0u;
+}
+
+// Next item for a workgroup whose own queue is `home`, or -1 when all are taken.
+__device__ __forceinline__ int next_item(int slot, int home, unsigned n_items) {
+  for (int k = 0; k < 8; ++k) {
+    const unsigned q = (unsigned)(home + k) & 7u;
+    const unsigned cnt = q < n_items ? (n_items - q + 7u) / 8u : 0u;   // items 8 t + q < n_items
+    if (cnt == 0u) continue;
+    const unsigned t = atomicAdd(&phase1_tickets[slot][q], 1u);
+    if (t < cnt) return (int)(8u * t + q);
+  }
+  return -1;
+}
+
+__device__ __forceinline__ void phase1_item(const Phase1Args& a, int hpw, int tpb, int n_hs, int id,
+                                            char* lds) {
   const Geom& g = a.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int col = lane & 15, j4 = lane >> 4;
   const int tm = 16 * (WG_BLOCKS / hpw);         // tokens per workgroup
 
-  // work decode: kv head fastest (one KV head per XCD when Hkv is a multiple of
-  // 8), then batch, head sub-group, tile within block (late = heavy first),
-  // block (block 0, the lightest, last)
-  int id = blockIdx.x;
+  // item decode: kv head fastest, then batch, head sub-group, tile within block
+  // (late = heavy first), block (block 0, the lightest, last)
   int kvh = id % g.Hkv; id /= g.Hkv;
   int beta = id % g.B; id /= g.B;
   int hs = id % n_hs; id /= n_hs;
@@ -740,6 +771,22 @@ __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1
   }
 }
 
+__global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1Args a, int hpw,
+                                                                          int tpb, int n_hs,
+                                                                          unsigned n_items, int slot) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  __shared__ int item;
+  for (;;) {
+    if (threadIdx.x == 0) item = next_item(slot, blockIdx.x & 7, n_items);
+    __syncthreads();
+    const int id = item;
+    __syncthreads();                 // everyone holds it before the next round overwrites it
+    if (id < 0) return;              // every queue is empty: uniform over the workgroup
+    phase1_item(a, hpw, tpb, n_hs, id, lds);
+    __syncthreads();                 // the item's LDS reads are done before the next item's DMAs
+  }
+}
+
 // ------------------------------------------------------------------ phase 2
 // Local attention (Eq. 1) and log-sum-exp (log of Eq. 2) of a row tile over one
 // split of the cache.  grid.x = ((batch * s_total + split) * n_hs + hs) * row_tiles + tile,
@@ -837,7 +884,18 @@ hipError_t launch_phase1_bf16(const Phase1Args& a, hipStream_t st) {
   hipError_t e = hipFuncSetAttribute((const void*)phase1_bf16_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
   if (e != hipSuccess) return e;
-  phase1_bf16_kernel<<<dim3((unsigned)wgs), NT, 4 * TILEB, st>>>(a, hpw, tpb, n_hs);
+  // one workgroup per CU (registers and LDS admit no more), never more than items
+  static std::atomic<unsigned> next_slot{0};
+  int dev = 0, n_cu = 0;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+  if (NW == 4) n_cu *= 2;
+  const unsigned resident = (unsigned)(wgs < n_cu ? wgs : n_cu);
+  if (resident == 0) return hipSuccess;
+  const int slot = (int)(next_slot.fetch_add(1u) % TICKET_SLOTS);
+  phase1_tickets_reset_kernel<<<1, 64, 0, st>>>(slot);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  phase1_bf16_kernel<<<dim3(resident), NT, 4 * TILEB, st>>>(a, hpw, tpb, n_hs, (unsigned)wgs, slot);
   return hipGetLastError();
 }
 
