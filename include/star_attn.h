@@ -16,7 +16,11 @@
  * Conventions
  *   - Every pointer is DEVICE memory owned by the caller unless it says "host".
  *     The library never allocates, frees or keeps a pointer after a call
- *     returns, and holds no state between calls.
+ *     returns.  Its only state is a set of 64 small work-queue counters in
+ *     static device memory that the bf16 phase-1 kernel draws its row tiles
+ *     from: every phase-1 call takes the next set in turn and clears it on the
+ *     stream before use, so up to 64 bf16 phase-1 calls of one process may be
+ *     in flight on a device at once (more would share a set and mis-schedule).
  *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t
  *     passed as void*, NULL = the default stream) and the function returns
  *     without synchronising.  Calls on one stream run in order.
