@@ -761,12 +761,20 @@ __device__ __forceinline__ void phase1_item(const Phase1Args& a, int hpw, int tp
     const int n_units = (wg_last - row0) * 16;            // 16-byte units per tensor
     char* kc = (char*)a.Kc + (((size_t)beta * g.Hkv + kvh) * (size_t)g.cap + row0) * ROWB;
     char* vc = (char*)a.Vc + (((size_t)beta * g.Hkv + kvh) * (size_t)g.cap + row0) * ROWB;
-    for (int u = tid; u < n_units; u += NT) {
-      size_t src = (size_t)(row0 + (u >> 4)) * kv_stride + (u & 15) * 16;
-      i32x4 kx = *(const i32x4*)(Kb + src);
-      i32x4 vx = *(const i32x4*)(Vb + src);
-      *(i32x4*)(kc + (size_t)u * 16) = kx;
-      *(i32x4*)(vc + (size_t)u * 16) = vx;
+    // two units per thread and pass, all four loads before the stores: one round trip
+    for (int u = tid; u < n_units; u += 2 * NT) {
+      const int u2 = u + NT;
+      const bool two = u2 < n_units;
+      const size_t s1 = (size_t)(row0 + (u >> 4)) * kv_stride + (u & 15) * 16;
+      const size_t s2 = two ? (size_t)(row0 + (u2 >> 4)) * kv_stride + (u2 & 15) * 16 : s1;
+      const i32x4 k1 = *(const i32x4*)(Kb + s1), v1 = *(const i32x4*)(Vb + s1);
+      const i32x4 k2 = *(const i32x4*)(Kb + s2), v2 = *(const i32x4*)(Vb + s2);
+      *(i32x4*)(kc + (size_t)u * 16) = k1;
+      *(i32x4*)(vc + (size_t)u * 16) = v1;
+      if (two) {
+        *(i32x4*)(kc + (size_t)u2 * 16) = k2;
+        *(i32x4*)(vc + (size_t)u2 * 16) = v2;
+      }
     }
   }
 }
