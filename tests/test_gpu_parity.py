@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2411_17116_amd as sa
 import workloads
 from tests import parity_harness as ph
 
@@ -104,6 +105,39 @@ def test_run_to_run_determinism():
         outs.append((run.O_ctx.clone(), run.LSE_ctx.clone(), O, Op, Lp, O1))
     for x, y in zip(*outs):
         assert torch.equal(x, y)
+
+
+def test_phase1_work_queues_across_many_launches_and_two_streams():
+    """The bf16 phase-1 kernel draws its row tiles from ticket queues that live in
+    64 slots of static device memory, taken in turn by the launches.  More than
+    64 launches in a row reuse the slots, and launches on two streams that run
+    at the same time hold different slots: every launch must give the bits of
+    the first."""
+    cfg = workloads.StarConfig("queues", "bf16", 1, 8, 2, 128, 3000, 512, 200, 1, 0, seed=17)
+    inp = workloads.make_inputs(cfg, "cuda")
+    run = ph.HipRun(cfg, inp)
+    run.phase1()
+    torch.cuda.synchronize()
+    O0, K0, V0 = run.O_ctx.clone(), run.Kc.clone(), run.Vc.clone()
+    for _ in range(70):                              # wraps around the 64 slots
+        run.O_ctx.zero_()
+        run.phase1()
+    torch.cuda.synchronize()
+    assert torch.equal(run.O_ctx, O0) and torch.equal(run.Kc, K0) and torch.equal(run.Vc, V0)
+    # two launches in flight at once, each with its own outputs
+    other = ph.HipRun(cfg, inp)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    s1.wait_stream(torch.cuda.current_stream())
+    s2.wait_stream(torch.cuda.current_stream())
+    for _ in range(4):
+        run.O_ctx.zero_()
+        other.O_ctx.zero_()
+        torch.cuda.synchronize()
+        sa.phase1(run.shape, inp.Q, inp.K, inp.V, run.O_ctx, run.Kc, run.Vc, stream=s1)
+        sa.phase1(other.shape, inp.Q, inp.K, inp.V, other.O_ctx, other.Kc, other.Vc, stream=s2)
+        torch.cuda.synchronize()
+        assert torch.equal(run.O_ctx, O0) and torch.equal(other.O_ctx, O0)
+        assert torch.equal(other.Kc[:, :, :cfg.L], K0[:, :, :cfg.L])
 
 
 @pytest.mark.parametrize("Hq,Hkv,lq", [(4, 1, 4), (4, 2, 5), (8, 1, 2), (6, 2, 3), (1, 1, 16)])
