@@ -629,7 +629,7 @@ def main():
                      "unit": "TFLOP/s", "frac": p1_tflops / MFMA_PEAK_TFLOPS[cfg.dtype],
                      "traffic": measured_traffic("phase1", cfg.name),
                      "note": "flops = 4 d per visible (query, key) pair; time = the phase-1 call "
-                             "(bf16: one kernel that attends and files K/V in the caches)"},
+                             "(bf16: a 4 us kernel that clears the work-queue tickets, then one kernel that attends and files K/V in the caches)"},
         "roofline_decode": {"bound": "hbm", "kernel": "decode_bf16_kernel" if cfg.dtype == "bf16" else "phase2_f32_kernel",
                             "achieved": dec_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": dec_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("decode", cfg.name),
