@@ -15,12 +15,15 @@
  *
  * Conventions
  *   - Every pointer is DEVICE memory owned by the caller unless it says "host".
- *     The library never allocates, frees or keeps a pointer after a call
- *     returns.  Its only state is a set of 64 small work-queue counters in
- *     static device memory that the bf16 phase-1 kernel draws its row tiles
- *     from: every phase-1 call takes the next set in turn and clears it on the
- *     stream before use, so up to 64 bf16 phase-1 calls of one process may be
- *     in flight on a device at once (more would share a set and mis-schedule).
+ *     The library never allocates device memory, frees or keeps a pointer
+ *     after a call returns.  The bf16 phase-1 kernel draws its row tiles from
+ *     eight work-queue counters; they live in the call's workspace.  A caller
+ *     that passes no workspace gets one of 64 sets in the library's static
+ *     device memory instead (its only state): a set is handed out again only
+ *     when the call that last used it has finished on the device, and a call
+ *     that finds all 64 in flight -- or whose stream is being captured into a
+ *     graph, where a set would be shared by every replay -- returns
+ *     STAR_ATTN_ERR_BUSY without enqueueing anything.
  *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t
  *     passed as void*, NULL = the default stream) and the function returns
  *     without synchronising.  Calls on one stream run in order.
@@ -29,8 +32,11 @@
  *     (bf16 storage, bf16 MFMA with fp32 accumulation and fp32 softmax).
  *     Partial outputs, LSE values and the workspace are always fp32.
  *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
- *   - All validation happens on the host before anything is enqueued; a
- *     non-zero return means no work was enqueued and no buffer was touched.
+ *   - All validation happens on the host before anything is enqueued: every
+ *     error code but STAR_ATTN_ERR_LAUNCH_FAILED means no work was enqueued and
+ *     no buffer was touched.  STAR_ATTN_ERR_LAUNCH_FAILED (the HIP runtime
+ *     refused a kernel launch) may leave earlier kernels of the call on the
+ *     stream, e.g. Q already rotated in place by a *_rope entry point.
  *   - Results are deterministic (no floating-point atomics).
  */
 #ifndef STAR_ATTN_H
@@ -48,7 +54,7 @@ enum {
   STAR_ATTN_BF16 = 1
 };
 
-/* Status codes: 0 = success, negative = error (nothing was enqueued). */
+/* Status codes: 0 = success, negative = error. */
 enum {
   STAR_ATTN_OK = 0,
   STAR_ATTN_ERR_INVALID_SHAPE = -1,        /* non-positive size, Hq % Hkv != 0, bad q_len/cache_len */
@@ -60,7 +66,11 @@ enum {
   STAR_ATTN_ERR_WORKSPACE_TOO_SMALL = -7,
   STAR_ATTN_ERR_LAUNCH_FAILED = -8,        /* the HIP runtime refused a launch */
   STAR_ATTN_ERR_MISALIGNED = -9,           /* a tensor pointer is not 16-byte aligned */
-  STAR_ATTN_ERR_INVALID_MODE = -10         /* anchor_mode is none of STAR_ATTN_ANCHOR_* */
+  STAR_ATTN_ERR_INVALID_MODE = -10,        /* anchor_mode is none of STAR_ATTN_ANCHOR_* */
+  STAR_ATTN_ERR_BUSY = -11                 /* bf16 phase 1 without a workspace: the library's own 64
+                                              sets of work-queue counters all belong to launches
+                                              still in flight, or the stream is being captured;
+                                              pass a workspace (nothing was enqueued) */
 };
 
 /* What prefixes every context block after the first in phase 1. */
@@ -94,8 +104,8 @@ typedef struct star_attn_shape {
 
 /*
  * Bytes of device workspace star_attn_phase2 needs for calls with
- * q_len <= max_q_len (split-KV partial outputs and their log-sum-exps).
- * star_attn_phase1 needs none.  Returns 0 for an invalid shape.
+ * q_len <= max_q_len (split-KV partial outputs and their log-sum-exps) on the
+ * current device.  Returns 0 for an invalid shape.
  */
 size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len);
 
@@ -117,7 +127,13 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
  *                 denominator of the scaled logits; may be NULL
  *   K_cache, V_cache  out  [B, Hkv, cache_capacity, d]; rows [0, L) are written,
  *                 the rest is left untouched
- *   workspace     unused by this call (may be NULL / 0)
+ *   workspace     bf16: at least star_attn_phase1_workspace_bytes(shape,
+ *                 STAR_ATTN_ANCHOR_FIRST) bytes (256), 16-byte aligned; it holds the
+ *                 launch's work-queue counters (cleared on the stream by the call,
+ *                 contents are scratch afterwards), so calls with workspaces of their
+ *                 own may overlap freely and may be captured into graphs.  NULL: the
+ *                 library's own counters are used (see Conventions;
+ *                 STAR_ATTN_ERR_BUSY when none is free).  fp32: unused.
  */
 int star_attn_phase1(const star_attn_shape* shape,
                      const void* Q, const void* K, const void* V,
@@ -153,9 +169,10 @@ int star_attn_phase1(const star_attn_shape* shape,
  *                 n = ceil(L / b) (PER_BLOCK; slice 0 is never read), dtype of the
  *                 inputs; read only in these modes with a > 0 (else may be NULL)
  *   workspace     at least star_attn_phase1_workspace_bytes(shape, mode) bytes,
- *                 256-byte aligned, scratch (only separately given anchors in fp32
- *                 need any: a head-major copy of them); unused and may be NULL / 0
- *                 when that size is 0
+ *                 256-byte aligned, scratch.  bf16: the work-queue counters, as in
+ *                 star_attn_phase1 (NULL selects the library's own).  fp32:
+ *                 a head-major copy of separately given anchors; unused and may be
+ *                 NULL / 0 when that size is 0
  *   other arguments as in star_attn_phase1
  * Errors as in star_attn_phase1, plus STAR_ATTN_ERR_INVALID_MODE and
  * STAR_ATTN_ERR_WORKSPACE_TOO_SMALL.
@@ -167,7 +184,8 @@ int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode,
                             void* K_cache, void* V_cache,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Workspace bytes star_attn_phase1_anchor needs (0 unless anchors are given separately in fp32; 0 for an invalid shape). */
+/* Workspace bytes of star_attn_phase1 / _anchor / _rope: 256 for bf16 (the launch's work-queue
+ * counters), the anchor copies for separately given anchors in fp32, else 0; 0 for an invalid shape. */
 size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode);
 
 /*
@@ -291,6 +309,26 @@ int star_attn_phase2_rope(const star_attn_shape* shape, double rope_theta, int64
 
 int star_attn_rope(const star_attn_shape* shape, int32_t n_heads, int64_t n_tokens, int64_t pos0,
                    double rope_theta, const void* X, void* Y, void* hip_stream);
+
+/*
+ * What a star_attn_phase2 call with these arguments would run (Section 2.2: how the
+ * cache is cut into the pieces whose pairs (A, lse) of Eq. 1-2 are merged by Eq. 3-4).
+ * For logs, benchmarks and tests that must know which kernel set-up they exercised.
+ * `out` is HOST memory.  Returns a status code; nothing is enqueued.
+ */
+typedef struct star_attn_plan_info {
+  int32_t decode;          /* 1: streaming split-KV kernel (G * q_len <= 16, bf16); 0: row-tiled kernel */
+  int32_t flat;            /* 1: splits ignore part boundaries (only without per-part outputs) */
+  int32_t n_splits;        /* splits per (batch, KV head) */
+  int32_t non_temporal;    /* 1: the decode kernel reads the cache with non-temporal loads */
+  int32_t steps_per_batch; /* decode kernel: 32-key steps loaded per batch (1 or 2); else 0 */
+  int32_t reserved;
+  int64_t split_len;       /* keys per split */
+  int64_t workspace_bytes; /* bytes of workspace this very call uses */
+} star_attn_plan_info;
+
+int star_attn_phase2_plan(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
+                          int want_parts, star_attn_plan_info* out);
 
 /* Static, NUL-terminated description of a status code (host memory, never freed). */
 const char* star_attn_status_string(int status);

@@ -48,6 +48,16 @@ class StarShape(ctypes.Structure):
                    float(softmax_scale), 0.0)
 
 
+class PlanInfo(ctypes.Structure):
+    """Mirror of `star_attn_plan_info`."""
+    _fields_ = [
+        ("decode", ctypes.c_int32), ("flat", ctypes.c_int32), ("n_splits", ctypes.c_int32),
+        ("non_temporal", ctypes.c_int32), ("steps_per_batch", ctypes.c_int32),
+        ("reserved", ctypes.c_int32), ("split_len", ctypes.c_int64),
+        ("workspace_bytes", ctypes.c_int64),
+    ]
+
+
 def lib_path() -> str:
     return os.path.join(_HERE, "libstarattn.so")
 
@@ -89,6 +99,8 @@ def load_library():
     lib.star_attn_merge.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp]
     lib.star_attn_status_string.restype = ctypes.c_char_p
     lib.star_attn_status_string.argtypes = [ctypes.c_int]
+    lib.star_attn_phase2_plan.restype = ctypes.c_int
+    lib.star_attn_phase2_plan.argtypes = [P, i64, i64, ctypes.c_int, ctypes.POINTER(PlanInfo)]
     lib.star_attn_kernel_path.restype = ctypes.c_char_p
     lib.star_attn_kernel_path.argtypes = [P]
     _LIB = lib
@@ -102,6 +114,14 @@ def status_string(code: int) -> str:
 def kernel_path(shape: StarShape) -> Optional[str]:
     r = load_library().star_attn_kernel_path(ctypes.byref(shape))
     return r.decode() if r else None
+
+
+def phase2_plan(shape: StarShape, cache_len: int, q_len: int, want_parts: bool = False) -> PlanInfo:
+    """star_attn_phase2_plan: what a phase-2 call with these arguments would run."""
+    info = PlanInfo()
+    _check(load_library().star_attn_phase2_plan(ctypes.byref(shape), int(cache_len), int(q_len),
+                                                int(bool(want_parts)), ctypes.byref(info)))
+    return info
 
 
 def workspace_bytes(shape: StarShape, max_q_len: int) -> int:
@@ -167,11 +187,12 @@ def phase1_anchor(shape: StarShape, anchor_mode: int, Q, K, V, O_ctx, K_cache, V
 
 
 def phase1_rope(shape: StarShape, rope_theta: float, Q, K, V, O_ctx, K_cache, V_cache, pos0=0,
-                LSE_ctx=None, stream=None) -> None:
+                LSE_ctx=None, workspace=None, stream=None) -> None:
     """star_attn_phase1_rope: phase 1 on unrotated Q (rotated in place) and K."""
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
     rc = load_library().star_attn_phase1_rope(
         ctypes.byref(shape), float(rope_theta), int(pos0), _ptr(Q), _ptr(K), _ptr(V), _ptr(O_ctx),
-        _ptr(LSE_ctx), _ptr(K_cache), _ptr(V_cache), None, 0, _stream(stream))
+        _ptr(LSE_ctx), _ptr(K_cache), _ptr(V_cache), _ptr(workspace), ws_n, _stream(stream))
     _check(rc)
 
 

@@ -6,7 +6,78 @@
 
 #include <math.h>
 
+#include <mutex>
+
 namespace star {
+
+// ---------------------------------------------------------------------------
+// Per-device facts and the library's only state: static device memory that
+// serves callers who hand in no workspace.
+// ---------------------------------------------------------------------------
+constexpr int MAX_DEVICES = 64;
+constexpr int TICKET_SLOTS = 64;      // fallback sets of phase-1 work-queue counters
+
+// Fallback work-queue counters of the bf16 phase-1 kernel (eight per launch),
+// used only when star_attn_phase1* gets no workspace.  In host code the name is
+// a stand-in: the device address comes from hipGetSymbolAddress, once per device
+// (see device_state()).
+static __device__ __align__(256) unsigned int phase1_ticket_slots[TICKET_SLOTS][8];
+
+struct DeviceState {
+  bool ready = false;
+  int n_cu = 0;
+  unsigned int* tickets = nullptr;          // device address of phase1_ticket_slots on this device
+  hipEvent_t slot_done[TICKET_SLOTS] = {};  // recorded behind the launch that last used a slot
+  bool slot_used[TICKET_SLOTS] = {};
+  unsigned next_slot = 0;
+};
+static DeviceState g_dev[MAX_DEVICES];
+static std::mutex g_dev_mu;
+
+// State of the current device (looked up once per device), or null if the HIP
+// runtime refuses.  Holds g_dev_mu only while it fills an entry.
+static DeviceState* device_state() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  DeviceState* d = &g_dev[dev];
+  std::lock_guard<std::mutex> lock(g_dev_mu);
+  if (d->ready) return d;
+  if (hipDeviceGetAttribute(&d->n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      d->n_cu <= 0)
+    return nullptr;
+  if (hipGetSymbolAddress((void**)&d->tickets, HIP_SYMBOL(phase1_ticket_slots)) != hipSuccess ||
+      !d->tickets)
+    return nullptr;
+  d->ready = true;
+  return d;
+}
+
+// Compute units of the current device; the MI355X's 256 when no device can be
+// asked (size queries still answer on a machine without a GPU).
+int device_cu_count() {
+  DeviceState* d = device_state();
+  return d ? d->n_cu : 256;
+}
+
+// A free set of fallback counters of the current device: one whose last launch
+// has finished.  -1 when all TICKET_SLOTS sets belong to launches still in flight.
+static int acquire_ticket_slot(DeviceState* d) {
+  std::lock_guard<std::mutex> lock(g_dev_mu);
+  for (int k = 0; k < TICKET_SLOTS; ++k) {
+    const int slot = (int)((d->next_slot + k) % TICKET_SLOTS);
+    if (d->slot_used[slot] && hipEventQuery(d->slot_done[slot]) != hipSuccess) {
+      (void)hipGetLastError();          // hipErrorNotReady is an answer, not a failure
+      continue;
+    }
+    if (!d->slot_done[slot] &&
+        hipEventCreateWithFlags(&d->slot_done[slot], hipEventDisableTiming) != hipSuccess)
+      return -1;
+    d->slot_used[slot] = true;
+    d->next_slot = (unsigned)(slot + 1);
+    return slot;
+  }
+  return -1;
+}
 
 static int validate_shape(const star_attn_shape* s) {
   if (!s) return STAR_ATTN_ERR_NULL_POINTER;
@@ -41,12 +112,12 @@ static Geom make_geom(const star_attn_shape* s) {
 static int64_t ceil_div(int64_t x, int64_t y) { return (x + y - 1) / y; }
 static int64_t round_up(int64_t x, int64_t y) { return ceil_div(x, y) * y; }
 
-// Workgroups of the decode kernel that are resident at once on an MI355X
-// (256 CUs): one split each under a flat plan.
+// Workgroups of the decode kernel that are resident at once on the current
+// device (256 CUs on an MI355X): one split each under a flat plan.
 static int64_t decode_slots(const Geom& g, int64_t total) {
-  return 256 * (int64_t)decode_workgroups_per_cu(decode_cache_resident(g, total));
+  return device_cu_count() * (int64_t)decode_workgroups_per_cu(decode_cache_resident(g, total));
 }
-constexpr int64_t DECODE_SLOTS_MAX = 256 * 4;
+static int64_t decode_slots_max() { return device_cu_count() * (int64_t)4; }
 
 // Split plan for a phase-2 call with q_len new tokens that can see `total`
 // cache rows.  Decode-sized calls (G * q_len rows fit one 16-column MFMA tile)
@@ -69,6 +140,7 @@ static bool make_plan(const star_attn_shape* s, int64_t q_len, int64_t total, bo
   if (p->decode && !want_parts) {
     int64_t pairs = (int64_t)g.B * g.Hkv;
     int64_t slots = decode_slots(g, total);
+    if (slots <= 0) return false;                  // no usable device
     int64_t s0 = slots / pairs > 1 ? slots / pairs : 1;
     split_len = round_up(ceil_div(total, s0), 32);
     if (split_len < 64) split_len = 64;
@@ -144,6 +216,9 @@ static size_t anchor_copy_bytes(const star_attn_shape* s, int anchor_mode) {
   return (n + 255) & ~(size_t)255;
 }
 
+// Bytes the bf16 phase-1 kernel's eight work-queue counters take in a workspace.
+constexpr size_t TICKET_BYTES = 256;
+
 }  // namespace star
 
 using namespace star;
@@ -163,7 +238,7 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
       if (!make_plan(shape, q, shape->cache_capacity, parts != 0, &p)) continue;
       if (p.flat) {   // a shorter cache may need one split more than the full one; bound it
         int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
-        int64_t s0 = DECODE_SLOTS_MAX / pairs > 1 ? DECODE_SLOTS_MAX / pairs : 1;
+        int64_t s0 = decode_slots_max() / pairs > 1 ? decode_slots_max() / pairs : 1;
         if (p.s_total < s0) p.s_total = (int32_t)s0;
       }
       size_t b = plan_bytes(shape, p, q);
@@ -178,10 +253,11 @@ size_t star_attn_workspace_bytes(const star_attn_shape* shape, int64_t max_q_len
 
 size_t star_attn_phase1_workspace_bytes(const star_attn_shape* shape, int anchor_mode) {
   if (validate_shape(shape) != STAR_ATTN_OK) return 0;
+  if (shape->dtype == STAR_ATTN_BF16) return TICKET_BYTES;     // the launch's work-queue counters
   const bool given = anchor_mode == STAR_ATTN_ANCHOR_EXTERNAL ||
                      anchor_mode == STAR_ATTN_ANCHOR_PER_BLOCK ||
                      anchor_mode == STAR_ATTN_ANCHOR_ALL_BLOCKS;
-  return given && shape->dtype == STAR_ATTN_F32 ? 2 * anchor_copy_bytes(shape, anchor_mode) : 0;
+  return given ? 2 * anchor_copy_bytes(shape, anchor_mode) : 0;
 }
 
 }  // extern "C"
@@ -221,6 +297,28 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
   }
   Geom g = make_geom(shape);
   hipStream_t st = (hipStream_t)hip_stream;
+  // The bf16 kernel's workgroups draw their row tiles from eight counters: the
+  // caller's workspace if there is one, else a free set of the library's own.
+  DeviceState* ds = nullptr;
+  unsigned int* tickets = nullptr;
+  int slot = -1;
+  if (shape->dtype == STAR_ATTN_BF16) {
+    if (workspace) {
+      if ((uintptr_t)workspace & 15u) return STAR_ATTN_ERR_MISALIGNED;
+      if (workspace_bytes < TICKET_BYTES) return STAR_ATTN_ERR_WORKSPACE_TOO_SMALL;
+    }
+    if (!(ds = device_state())) return STAR_ATTN_ERR_LAUNCH_FAILED;
+    if (workspace) {
+      tickets = (unsigned int*)workspace;
+    } else {
+      // a captured launch would carry its set into every replay of the graph
+      hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+      if (hipStreamIsCapturing(st, &cap) != hipSuccess) (void)hipGetLastError();
+      if (cap != hipStreamCaptureStatusNone) return STAR_ATTN_ERR_BUSY;
+      if ((slot = acquire_ticket_slot(ds)) < 0) return STAR_ATTN_ERR_BUSY;
+      tickets = ds->tickets + 8 * slot;
+    }
+  }
   // Algorithm 1: keep the K/V of every block once (anchor copies never exist here).
   // The bf16 attention kernel reads plain inputs where they are and files them in
   // the caches itself; rotated keys and the fp32 kernel go through the caches.
@@ -242,6 +340,8 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
   a.anchor_mode = anchor_mode; a.Ka = K_anchor; a.Va = V_anchor;
   a.Kin = fused_cache_write ? K : nullptr;
   a.Vin = fused_cache_write ? V : nullptr;
+  a.tickets = tickets;
+  a.n_cu = ds ? ds->n_cu : 0;
   if (ext_copy) {
     // the separately given anchors, head-major like the caches: [B, Hkv, n_anchor * a, d]
     // (the [B, n_anchor, a, Hkv, d] input is [B, n_anchor * a, Hkv, d] token-major)
@@ -255,6 +355,8 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
     a.Ka = wk; a.Va = wv;
   }
   hipError_t e = shape->dtype == STAR_ATTN_F32 ? launch_phase1_f32(a, st) : launch_phase1_bf16(a, st);
+  // the library's own counters are free again once everything enqueued so far is done
+  if (slot >= 0 && hipEventRecord(ds->slot_done[slot], st) != hipSuccess) e = hipErrorUnknown;
   return e == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
 }
 
@@ -272,19 +374,18 @@ int star_attn_phase1_anchor(const star_attn_shape* shape, int anchor_mode, const
 int star_attn_phase1(const star_attn_shape* shape, const void* Q, const void* K, const void* V,
                      void* O_ctx, float* LSE_ctx, void* K_cache, void* V_cache,
                      void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   return phase1_impl(shape, STAR_ATTN_ANCHOR_FIRST, nullptr, const_cast<void*>(Q), K, V, nullptr,
-                     nullptr, O_ctx, LSE_ctx, K_cache, V_cache, nullptr, 0, hip_stream);
+                     nullptr, O_ctx, LSE_ctx, K_cache, V_cache, workspace, workspace_bytes,
+                     hip_stream);
 }
 
 int star_attn_phase1_rope(const star_attn_shape* shape, double rope_theta, int64_t pos0, void* Q,
                           const void* K, const void* V, void* O_ctx, float* LSE_ctx,
                           void* K_cache, void* V_cache, void* workspace, size_t workspace_bytes,
                           void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Rope rope = {rope_theta, pos0};
   return phase1_impl(shape, STAR_ATTN_ANCHOR_FIRST, &rope, Q, K, V, nullptr, nullptr, O_ctx,
-                     LSE_ctx, K_cache, V_cache, nullptr, 0, hip_stream);
+                     LSE_ctx, K_cache, V_cache, workspace, workspace_bytes, hip_stream);
 }
 
 int star_attn_rope(const star_attn_shape* shape, int32_t n_heads, int64_t n_tokens, int64_t pos0,
@@ -455,8 +556,33 @@ const char* star_attn_status_string(int status) {
     case STAR_ATTN_ERR_LAUNCH_FAILED: return "kernel launch failed";
     case STAR_ATTN_ERR_MISALIGNED: return "pointer not sufficiently aligned";
     case STAR_ATTN_ERR_INVALID_MODE: return "unknown anchor mode";
+    case STAR_ATTN_ERR_BUSY:
+      return "no workspace given and the library's own work-queue counters are all in flight "
+             "(or the stream is being captured)";
     default: return "unknown status";
   }
+}
+
+int star_attn_phase2_plan(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
+                          int want_parts, star_attn_plan_info* out) {
+  int rc = validate_shape(shape);
+  if (rc != STAR_ATTN_OK) return rc;
+  if (!out) return STAR_ATTN_ERR_NULL_POINTER;
+  if (q_len <= 0 || q_len > (1 << 20) || cache_len < shape->ctx_len) return STAR_ATTN_ERR_INVALID_SHAPE;
+  const int64_t total = cache_len + q_len;
+  if (total > shape->cache_capacity) return STAR_ATTN_ERR_CACHE_OVERFLOW;
+  SplitPlan plan;
+  if (!make_plan(shape, q_len, total, want_parts != 0, &plan)) return STAR_ATTN_ERR_INVALID_SHAPE;
+  const bool resident = decode_cache_resident(make_geom(shape), total);
+  out->decode = plan.decode;
+  out->flat = plan.flat;
+  out->n_splits = plan.s_total;
+  out->non_temporal = plan.decode && !resident ? 1 : 0;
+  out->steps_per_batch = plan.decode ? (resident ? 1 : 2) : 0;
+  out->reserved = 0;
+  out->split_len = plan.split_len;
+  out->workspace_bytes = (int64_t)plan_bytes(shape, plan, q_len);
+  return STAR_ATTN_OK;
 }
 
 const char* star_attn_kernel_path(const star_attn_shape* shape) {

@@ -49,7 +49,8 @@
 //   * Phase 1 is launched with one workgroup per CU; the workgroups draw their
 //     work items (a row tile of one block and KV head) from eight ticket queues,
 //     each XCD from its own first (one KV head per XCD's L2 when Hkv is a
-//     multiple of 8) and from the others once that is empty.
+//     multiple of 8) and from the others once that is empty.  The queue counters
+//     are the launch's own (Phase1Args::tickets).
 #include "star_internal.h"
 
 #include <atomic>
@@ -635,23 +636,20 @@ __device__ __forceinline__ void load_q(WaveState& w, int rb, const char* qrow, i
 // next item of its XCD's queue until that is empty, then of the other queues: the
 // XCDs of one chip differ by a few per cent in clock under the power limit, and
 // with a fixed share each the launch would last as long as the slowest needs.
-// Launches take the ticket slots in turn (a launch's first kernel clears its
-// slot), so up to TICKET_SLOTS phase-1 launches of one process may be in flight
-// on a device at once.
-constexpr int TICKET_SLOTS = 64;
-__device__ unsigned int phase1_tickets[TICKET_SLOTS][8];
-
-__global__ void phase1_tickets_reset_kernel(int slot) {
-  if (threadIdx.x < 8) phase1_tickets[slot][threadIdx.x] = 0u;
+// The eight counters belong to the launch (the caller's workspace, or a set of
+// the library's own that no launch in flight holds); a one-workgroup kernel in
+// front of the launch clears them.
+__global__ void phase1_tickets_reset_kernel(unsigned int* tickets) {
+  if (threadIdx.x < 8) tickets[threadIdx.x] = 0u;
 }
 
 // Next item for a workgroup whose own queue is `home`, or -1 when all are taken.
-__device__ __forceinline__ int next_item(int slot, int home, unsigned n_items) {
+__device__ __forceinline__ int next_item(unsigned int* tickets, int home, unsigned n_items) {
   for (int k = 0; k < 8; ++k) {
     const unsigned q = (unsigned)(home + k) & 7u;
     const unsigned cnt = q < n_items ? (n_items - q + 7u) / 8u : 0u;   // items 8 t + q < n_items
     if (cnt == 0u) continue;
-    const unsigned t = atomicAdd(&phase1_tickets[slot][q], 1u);
+    const unsigned t = atomicAdd(&tickets[q], 1u);
     if (t < cnt) return (int)(8u * t + q);
   }
   return -1;
@@ -781,11 +779,11 @@ __device__ __forceinline__ void phase1_item(const Phase1Args& a, int hpw, int tp
 
 __global__ __launch_bounds__(NT, NW == 4 ? 2 : 1) void phase1_bf16_kernel(Phase1Args a, int hpw,
                                                                           int tpb, int n_hs,
-                                                                          unsigned n_items, int slot) {
+                                                                          unsigned n_items) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   __shared__ int item;
   for (;;) {
-    if (threadIdx.x == 0) item = next_item(slot, blockIdx.x & 7, n_items);
+    if (threadIdx.x == 0) item = next_item(a.tickets, blockIdx.x & 7, n_items);
     __syncthreads();
     const int id = item;
     __syncthreads();                 // everyone holds it before the next round overwrites it
@@ -879,6 +877,20 @@ int flash_heads_per_workgroup(int G) {
 }
 int flash_tokens_per_workgroup(int G) { return 16 * (WG_BLOCKS / flash_heads_per_workgroup(G)); }
 
+// The kernels' 64 KiB tile ring is dynamic LDS; the runtime wants to be told
+// once per kernel and device that a launch may ask for that much.
+enum { ATTR_PHASE1 = 0, ATTR_PHASE2_ROWS = 1 };
+static hipError_t allow_tile_ring(int which, const void* kernel) {
+  static std::atomic<bool> done[2][64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && done[which][dev].load(std::memory_order_acquire)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
+  if (e == hipSuccess && dev >= 0 && dev < 64) done[which][dev].store(true, std::memory_order_release);
+  return e;
+}
+
 hipError_t launch_phase1_bf16(const Phase1Args& a, hipStream_t st) {
   const Geom& g = a.g;
   int hpw = flash_heads_per_workgroup(g.G);
@@ -889,21 +901,17 @@ hipError_t launch_phase1_bf16(const Phase1Args& a, hipStream_t st) {
   int tpb = (int)((bmax + tm - 1) / tm);
   int64_t wgs = (int64_t)g.Hkv * g.B * n_hs * tpb * n;
   if (wgs > 0x7fffffff) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute((const void*)phase1_bf16_kernel,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
+  hipError_t e = allow_tile_ring(ATTR_PHASE1, (const void*)phase1_bf16_kernel);
   if (e != hipSuccess) return e;
   // one workgroup per CU (registers and LDS admit no more), never more than items
-  static std::atomic<unsigned> next_slot{0};
-  int dev = 0, n_cu = 0;
-  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-  if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+  int n_cu = a.n_cu;
+  if (n_cu <= 0 || !a.tickets) return hipErrorInvalidValue;
   if (NW == 4) n_cu *= 2;
   const unsigned resident = (unsigned)(wgs < n_cu ? wgs : n_cu);
   if (resident == 0) return hipSuccess;
-  const int slot = (int)(next_slot.fetch_add(1u) % TICKET_SLOTS);
-  phase1_tickets_reset_kernel<<<1, 64, 0, st>>>(slot);
+  phase1_tickets_reset_kernel<<<1, 64, 0, st>>>(a.tickets);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  phase1_bf16_kernel<<<dim3(resident), NT, 4 * TILEB, st>>>(a, hpw, tpb, n_hs, (unsigned)wgs, slot);
+  phase1_bf16_kernel<<<dim3(resident), NT, 4 * TILEB, st>>>(a, hpw, tpb, n_hs, (unsigned)wgs);
   return hipGetLastError();
 }
 
@@ -915,8 +923,7 @@ hipError_t launch_phase2_rows_bf16(const Phase2Args& a, hipStream_t st) {
   int row_tiles = (a.q_len + tm - 1) / tm;
   int64_t gx = (int64_t)g.B * a.plan.s_total * n_hs * row_tiles;
   if (gx > 0x7fffffff || g.Hkv > 65535) return hipErrorInvalidValue;
-  hipError_t e = hipFuncSetAttribute((const void*)phase2_rows_bf16_kernel,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILEB);
+  hipError_t e = allow_tile_ring(ATTR_PHASE2_ROWS, (const void*)phase2_rows_bf16_kernel);
   if (e != hipSuccess) return e;
   phase2_rows_bf16_kernel<<<dim3((unsigned)gx, (unsigned)g.Hkv), NT, 4 * TILEB, st>>>(a, hpw, n_hs,
                                                                                       row_tiles);

@@ -58,6 +58,8 @@ struct Phase1Args {
                         // kernel, token-major [B, n_anchor, a, Hkv, d] for the bf16 one
   const void* Kin;      // bf16 kernel: the token-major inputs [B, L, Hkv, d] to read keys /
   const void* Vin;      // values from (and to file in the caches); null: read the caches
+  unsigned int* tickets;  // bf16 kernel: this launch's eight work-queue counters (device memory)
+  int32_t n_cu;           // bf16 kernel: compute units of the device the call runs on
 };
 
 // Anchor key rows [*lo, *hi) of 0-based block i, and whether they index the
@@ -150,6 +152,9 @@ __host__ __device__ inline void split_range(const SplitPlan& p, int64_t L, int64
 // workgroup, and tokens per workgroup (the split plan sizes its grids with them).
 int flash_heads_per_workgroup(int G);
 int flash_tokens_per_workgroup(int G);
+
+// Compute units of the current device (cached per device; 0 if the runtime refuses).
+int device_cu_count();
 
 // Host-side launchers (each returns the hipError_t of its launch).
 // K and / or V (a null source is skipped) into rows [dst_row, dst_row + n_tokens).

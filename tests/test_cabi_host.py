@@ -16,7 +16,7 @@ HEADER = os.path.join(ROOT, "include", "star_attn.h")
 # status codes as the header defines them
 ERR = dict(INVALID_SHAPE=-1, NULL_POINTER=-2, UNSUPPORTED_HEAD_DIM=-3, UNSUPPORTED_DTYPE=-4,
            ANCHOR_GT_BLOCK=-5, CACHE_OVERFLOW=-6, WORKSPACE_TOO_SMALL=-7, LAUNCH_FAILED=-8,
-           MISALIGNED=-9, INVALID_MODE=-10)
+           MISALIGNED=-9, INVALID_MODE=-10, BUSY=-11)
 
 
 @pytest.fixture(scope="module")
@@ -42,7 +42,7 @@ def test_header_symbols_are_exported(lib):
                           "star_attn_status_string", "star_attn_kernel_path",
                           "star_attn_phase1_anchor", "star_attn_phase1_workspace_bytes",
                           "star_attn_phase1_rope", "star_attn_phase2_rope", "star_attn_rope",
-                          "star_attn_phase2_partial", "star_attn_merge"}
+                          "star_attn_phase2_partial", "star_attn_merge", "star_attn_phase2_plan"}
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -149,6 +149,34 @@ def test_workspace_query_covers_every_call_size(lib):
         assert sizes == sorted(sizes), "requirement must not shrink as max_q_len grows"
 
 
+def test_plan_query(lib):
+    """star_attn_phase2_plan answers on the host: decode-sized calls stream the
+    cache, flat only without per-part outputs; caches beyond 192 MiB of K + V are
+    read with non-temporal loads, two steps per batch."""
+    small = good_shape()
+    p = sa.phase2_plan(small, small.ctx_len, 1)
+    assert (p.decode, p.flat, p.non_temporal, p.steps_per_batch) == (1, 1, 0, 1)
+    assert p.workspace_bytes <= sa.workspace_bytes(small, 1)
+    p = sa.phase2_plan(small, small.ctx_len, 1, want_parts=True)
+    assert (p.decode, p.flat) == (1, 0) and p.n_splits >= 5          # 4 blocks + the tail
+    p = sa.phase2_plan(small, small.ctx_len, 64)
+    assert (p.decode, p.flat, p.steps_per_batch) == (0, 0, 0)
+    c3 = good_shape(n_q_heads=32, n_kv_heads=8, ctx_len=131072, block=16384, anchor=16384,
+                    cache_capacity=131072 + 384)
+    p = sa.phase2_plan(c3, 131072 + 256, 1)
+    assert (p.decode, p.flat, p.non_temporal, p.steps_per_batch) == (1, 1, 1, 2)
+    assert p.n_splits == 96                                           # 256 CUs x 3 over 8 KV heads
+    p = sa.phase2_plan(c3, 131072 + 256, 1, want_parts=True)
+    assert (p.decode, p.flat, p.non_temporal) == (1, 0, 1)
+    f32 = good_shape(dtype="fp32", head_dim=64)
+    assert sa.phase2_plan(f32, f32.ctx_len, 1).decode == 0
+    info = binding.PlanInfo()
+    call = lib.star_attn_phase2_plan
+    assert call(ctypes.byref(small), small.ctx_len, 0, 0, ctypes.byref(info)) == ERR["INVALID_SHAPE"]
+    assert call(ctypes.byref(small), small.cache_capacity, 1, 0, ctypes.byref(info)) == ERR["CACHE_OVERFLOW"]
+    assert call(ctypes.byref(small), small.ctx_len, 1, 0, None) == ERR["NULL_POINTER"]
+
+
 def test_kernel_path_names(lib):
     assert sa.kernel_path(good_shape()) == "bf16-mfma"
     assert sa.kernel_path(good_shape(dtype="fp32", head_dim=64)) == "f32-valu"
@@ -172,8 +200,12 @@ def test_phase1_anchor_variant_arguments(lib):
         assert _p1a(lib, shape, mode, Q=None) == ERR["NULL_POINTER"]
         assert _p1a(lib, shape, mode, Kc=0x1004) == ERR["MISALIGNED"]
     # the external anchor needs its tensors; the fp32 path also needs a workspace
-    # for their head-major copy (the bf16 kernel reads the tensors where they are)
-    assert sa.binding.phase1_workspace_bytes(shape, EXT) == 0
+    # for their head-major copy (the bf16 kernel reads the tensors where they are:
+    # its workspace is the launch's work-queue counters in every mode)
+    assert sa.binding.phase1_workspace_bytes(shape, EXT) == 256
+    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_FIRST) == 256
+    assert _p1a(lib, shape, EXT, ws=0x1008, ws_bytes=256) == ERR["MISALIGNED"]
+    assert _p1a(lib, shape, EXT, ws_bytes=64) == ERR["WORKSPACE_TOO_SMALL"]
     assert _p1a(lib, shape, EXT, Ka=None) == ERR["NULL_POINTER"]
     assert _p1a(lib, shape, EXT, Va=None) == ERR["NULL_POINTER"]
     assert _p1a(lib, shape, EXT, Ka=0x1008) == ERR["MISALIGNED"]
@@ -185,7 +217,7 @@ def test_phase1_anchor_variant_arguments(lib):
     assert sa.binding.phase1_workspace_bytes(good_shape(batch=0), EXT) == 0
     # one anchor per block: n = 4 of them
     assert sa.binding.phase1_workspace_bytes(f32, binding.ANCHOR_PER_BLOCK) == 4 * need
-    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_PER_BLOCK) == 0
+    assert sa.binding.phase1_workspace_bytes(shape, binding.ANCHOR_PER_BLOCK) == 256
     assert _p1a(lib, shape, binding.ANCHOR_PER_BLOCK, Ka=None) == ERR["NULL_POINTER"]
     assert _p1a(lib, f32, binding.ANCHOR_PER_BLOCK, ws_bytes=need) == ERR["WORKSPACE_TOO_SMALL"]
     assert _p1a(lib, f32, EXT, Ka=None, ws_bytes=need) == ERR["NULL_POINTER"]
@@ -195,7 +227,7 @@ def test_phase1_anchor_variant_arguments(lib):
     # a host's share takes one anchor, like EXTERNAL
     ALL = binding.ANCHOR_ALL_BLOCKS
     assert sa.binding.phase1_workspace_bytes(f32, ALL) == need
-    assert sa.binding.phase1_workspace_bytes(shape, ALL) == 0
+    assert sa.binding.phase1_workspace_bytes(shape, ALL) == 256
     assert _p1a(lib, shape, ALL, Ka=None) == ERR["NULL_POINTER"]
     assert _p1a(lib, shape, ALL, Va=0x1008) == ERR["MISALIGNED"]
     assert _p1a(lib, f32, ALL, ws_bytes=need - 1) == ERR["WORKSPACE_TOO_SMALL"]
@@ -300,6 +332,7 @@ def test_header_is_plain_c(tmp_path):
         "  rc |= star_attn_rope(&s, 1, 1, 0, 10000.0, 0, 0, 0);\n"
         "  rc |= star_attn_phase2_partial(&s, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
         "  rc |= star_attn_merge(&s, 1, 1, 0, 0, 0, 0, 0, 0);\n"
+        "  { star_attn_plan_info pi; rc |= star_attn_phase2_plan(&s, 0, 1, 0, &pi); }\n"
         "  return (rc != 0 && star_attn_workspace_bytes(&s, 1) == 0 &&\n"
         "          star_attn_phase1_workspace_bytes(&s, 0) == 0 &&\n"
         "          star_attn_status_string(rc) != 0 && star_attn_kernel_path(&s) == 0) ? 0 : 1;\n"

@@ -67,3 +67,42 @@ def test_decode_steps_replayed_from_a_graph_match_eager(with_query):
         if with_query:
             assert torch.equal(Oq, want_q), f"replay {rep}, query call"
         assert torch.equal(run.Kc, want_K)
+
+
+def test_phase1_captured_with_its_own_workspace_and_refused_without():
+    """Phase 1 in a graph: with a workspace the launch's work-queue counters are
+    the caller's, so the captured launch can be replayed (every replay gives the
+    eager bits); without one the library would have to bake one of its static
+    counter sets into the graph, and refuses with STAR_ATTN_ERR_BUSY instead."""
+    cfg = workloads.StarConfig("graph1", "bf16", 1, 8, 2, 128, 4000, 1024, 600, 1, 0, seed=23)
+    inp = workloads.make_inputs(cfg, "cuda")
+    run = ph.HipRun(cfg, inp, "cuda")
+    run.phase1()
+    torch.cuda.synchronize()
+    want_O, want_L, want_K = run.O_ctx.clone(), run.LSE_ctx.clone(), run.Kc.clone()
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run.phase1()                              # warm-up on the capture stream
+    side.synchronize()
+    refused = None
+    with torch.cuda.graph(graph, stream=side):
+        try:
+            run.phase1(own_workspace=False)
+        except sa.StarAttnError as e:
+            refused = e.code
+        run.phase1()
+    assert refused == -11, refused                # STAR_ATTN_ERR_BUSY, nothing was captured for it
+    for rep in range(3):
+        print(f"replay {rep}", flush=True)
+        run.O_ctx.fill_(7.0)
+        run.LSE_ctx.fill_(7.0)
+        run.Kc.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(run.O_ctx, want_O), f"replay {rep}"
+        assert torch.equal(run.LSE_ctx, want_L), f"replay {rep}"
+        assert torch.equal(run.Kc, want_K), f"replay {rep}"

@@ -76,6 +76,19 @@ def _rope_path(cfg, theta, pos0, triples=None, heads=None, decode_steps=None):
     el = np.abs(run.LSE_ctx[bi, hi, ri].cpu().numpy() - L_ref).max()
     print(f"   phase 1: max|dO|={eo:.3g} max|dLSE|={el:.3g}", flush=True)
     assert eo <= tol["o"] and el <= tol["lse"]
+    # For the record (not asserted): the same rows against the oracle WITHOUT the
+    # storage rounding of the rotated q and k, i.e. attention on the exact fp64
+    # rotation.  The difference to the figures above is what rounding the rotated
+    # tensors to the storage dtype costs -- input quantisation, not compute error.
+    sub = triples if len(triples) <= 4096 else triples[:: len(triples) // 4096 + 1]
+    O_u, L_u = so.phase1_rope_rows(ph.LazyTensor(Q0), ph.LazyTensor(inp.K), ph.LazyTensor(inp.V),
+                                   sub, cfg.b, cfg.a, theta, pos0=pos0, storage=None)
+    si = torch.tensor(sub, dtype=torch.long, device="cuda")
+    sb, sh, sr = si.unbind(1)
+    eo_u = np.abs(run.O_ctx[sb, sr, sh].float().cpu().numpy() - O_u).max()
+    el_u = np.abs(run.LSE_ctx[sb, sh, sr].cpu().numpy() - L_u).max()
+    print(f"   phase 1 against the unrounded fp64 rotation ({len(sub)} rows, not asserted): "
+          f"max|dO|={eo_u:.3g} max|dLSE|={el_u:.3g}", flush=True)
     # Q was rotated in place; the cache holds rotated K and plain V (sampled heads)
     rows = sorted({p for _, _, p in triples})[:64]
     pos = pos0 + np.asarray(rows)
