@@ -101,7 +101,7 @@ def run_step(cfg, shape, inp, bufs, timer, sections=("phase1", "query", "decode"
     the only thing the reported numbers use) is the whole path."""
     e = timer.start()
     if "phase1" in sections:
-        sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+        sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"], workspace=bufs["ws1"])
     i_p1 = timer.stop(e)
     cache_len = cfg.L
     e = timer.start()
@@ -244,14 +244,14 @@ def sustained_phase1(cfg, shape, inp, bufs, poller, seconds=2.0):
     that fall inside that window."""
     t = Timer()
     e = t.start()
-    sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+    sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"], workspace=bufs["ws1"])
     i = t.stop(e)
     torch.cuda.synchronize()
     n = max(3, int(seconds * 1e3 / max(t.ms(i), 1e-3)))
     t0 = time.time()
     e = t.start()
     for _ in range(n):
-        sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+        sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"], workspace=bufs["ws1"])
     i = t.stop(e)
     torch.cuda.synchronize()
     t1 = time.time()
@@ -373,7 +373,7 @@ def block_sweep(cfg, inp, bufs):
         idx = []
         for _ in range(2):
             e = t.start()
-            sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+            sa.phase1(shape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"], workspace=bufs["ws1"])
             idx.append(t.stop(e))
         torch.cuda.synchronize()
         ms = min(t.ms(i) for i in idx)
@@ -571,6 +571,9 @@ def main():
     bufs = {
         "Kc": Kc, "Vc": Vc, "O_ctx": torch.empty_like(inp.Q), "Oq": torch.empty_like(inp.Qq),
         "ws": sa.alloc_workspace(shape, max(cfg.lq, 1)),
+        # phase 1's own workspace: the launch's work-queue counters (bf16)
+        "ws1": torch.empty(max(sa.phase1_workspace_bytes(shape, sa.ANCHOR_FIRST), 256),
+                           dtype=torch.uint8, device="cuda"),
         "Qd": [inp.Qd[:, t:t + 1].contiguous() for t in range(cfg.nd)],
         "Kd": [inp.Kd[:, t:t + 1].contiguous() for t in range(cfg.nd)],
         "Vd": [inp.Vd[:, t:t + 1].contiguous() for t in range(cfg.nd)],
@@ -646,7 +649,8 @@ def main():
         t = Timer()
         for _ in range(2):
             e = t.start()
-            sa.phase1(fshape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"])
+            sa.phase1(fshape, inp.Q, inp.K, inp.V, bufs["O_ctx"], bufs["Kc"], bufs["Vc"],
+                      workspace=bufs["ws1"])
             t.stop(e)
         torch.cuda.synchronize()
         f_ms = t.ms(1)
