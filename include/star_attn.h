@@ -221,6 +221,35 @@ int star_attn_phase2(const star_attn_shape* shape,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * star_attn_phase2 for callers that can neither allocate nor bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same computation, same kernels and the same bits as star_attn_phase2
+ * without per-part outputs; the per-split pairs that call keeps in its workspace
+ * go to a static device array of STAR_ATTN_STATIC_SCRATCH_BYTES inside the
+ * library instead.  The call allocates and frees nothing (the array's device
+ * address is looked up once per device, on the first call there).
+ *
+ *   - The scratch a call needs is star_attn_phase2_plan(...).workspace_bytes: at
+ *     most 8.5 MB for any decode-sized call (G * q_len <= 16) on an MI355X, 0.2 to
+ *     tens of MB for query encoding.  A call that needs more than
+ *     STAR_ATTN_STATIC_SCRATCH_BYTES is refused with
+ *     STAR_ATTN_ERR_WORKSPACE_TOO_SMALL before anything is enqueued.
+ *   - Every call on a GPU shares that GPU's one array: calls on one stream run in
+ *     order and are safe; calls that overlap on one GPU (two streams, two
+ *     threads, two graphs replayed at once) race on it and give wrong results.
+ *     Nothing in it has to start at zero and nothing in it survives a call.
+ *   - Each GPU the process uses holds its own 16 MiB copy until the process ends.
+ * Arguments and errors otherwise as in star_attn_phase2.
+ */
+#define STAR_ATTN_STATIC_SCRATCH_BYTES (16u << 20)
+
+int star_attn_phase2_static(const star_attn_shape* shape,
+                            int64_t cache_len, int64_t q_len,
+                            const void* Qq, const void* Kq, const void* Vq,
+                            void* K_cache, void* V_cache,
+                            void* O, void* hip_stream);
+
+/*
  * Phase 2 on one host of several (Section 2.2; Algorithm 2).
  *
  * When the cache is spread over hosts, the new tokens' queries go to every

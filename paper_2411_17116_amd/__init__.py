@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     BF16, F32, ANCHOR_FIRST, ANCHOR_PREVIOUS, ANCHOR_EXTERNAL, ANCHOR_PER_BLOCK, ANCHOR_ALL_BLOCKS,
     StarAttnError, StarShape, lib_path, load_library, phase1, phase1_anchor, phase1_rope,
     phase1_workspace_bytes, phase2, phase2_partial, phase2_rope, merge, rope, status_string,
-    workspace_bytes, kernel_path, alloc_cache, alloc_workspace, phase2_plan, PlanInfo,
+    workspace_bytes, kernel_path, alloc_cache, alloc_workspace, phase2_plan, PlanInfo, phase2_static, STATIC_SCRATCH_BYTES,
 )

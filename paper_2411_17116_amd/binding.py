@@ -93,6 +93,8 @@ def load_library():
     lib.star_attn_rope.argtypes = [P, ctypes.c_int32, i64, i64, dbl, vp, vp, vp]
     lib.star_attn_phase2.restype = ctypes.c_int
     lib.star_attn_phase2.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.star_attn_phase2_static.restype = ctypes.c_int
+    lib.star_attn_phase2_static.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.star_attn_phase2_partial.restype = ctypes.c_int
     lib.star_attn_phase2_partial.argtypes = [P, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.star_attn_merge.restype = ctypes.c_int
@@ -226,6 +228,20 @@ def phase2(shape: StarShape, cache_len: int, Qq, Kq, Vq, K_cache, V_cache, O, wo
         ctypes.byref(shape), int(cache_len), int(q_len), _ptr(Qq), _ptr(Kq), _ptr(Vq),
         _ptr(K_cache), _ptr(V_cache), _ptr(O_part), _ptr(LSE_part), _ptr(O),
         _ptr(workspace), ws_n, _stream(stream))
+    _check(rc)
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def phase2_static(shape: StarShape, cache_len: int, Qq, Kq, Vq, K_cache, V_cache, O,
+                  stream=None) -> None:
+    """star_attn_phase2_static: star_attn_phase2 with the library's static scratch
+    in place of a workspace (allocates nothing; calls must not overlap on a GPU)."""
+    q_len = Qq.shape[1]
+    rc = load_library().star_attn_phase2_static(
+        ctypes.byref(shape), int(cache_len), int(q_len), _ptr(Qq), _ptr(Kq), _ptr(Vq),
+        _ptr(K_cache), _ptr(V_cache), _ptr(O), _stream(stream))
     _check(rc)
 
 

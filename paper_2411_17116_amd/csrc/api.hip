@@ -23,10 +23,17 @@ constexpr int TICKET_SLOTS = 64;      // fallback sets of phase-1 work-queue cou
 // (see device_state()).
 static __device__ __align__(256) unsigned int phase1_ticket_slots[TICKET_SLOTS][8];
 
+// Scratch of star_attn_phase2_static (per-split outputs and log-sum-exps), for
+// callers that cannot bring a workspace.  Every GPU the library runs on holds
+// its own copy until the process ends.  As above, host code uses the address
+// hipGetSymbolAddress returns, never the name.
+static __device__ __align__(256) unsigned char scratch[STAR_ATTN_STATIC_SCRATCH_BYTES];
+
 struct DeviceState {
   bool ready = false;
   int n_cu = 0;
   unsigned int* tickets = nullptr;          // device address of phase1_ticket_slots on this device
+  unsigned char* scratch_ptr = nullptr;     // device address of scratch on this device
   hipEvent_t slot_done[TICKET_SLOTS] = {};  // recorded behind the launch that last used a slot
   bool slot_used[TICKET_SLOTS] = {};
   unsigned next_slot = 0;
@@ -46,7 +53,8 @@ static DeviceState* device_state() {
       d->n_cu <= 0)
     return nullptr;
   if (hipGetSymbolAddress((void**)&d->tickets, HIP_SYMBOL(phase1_ticket_slots)) != hipSuccess ||
-      !d->tickets)
+      hipGetSymbolAddress((void**)&d->scratch_ptr, HIP_SYMBOL(scratch)) != hipSuccess ||
+      !d->tickets || !d->scratch_ptr)
     return nullptr;
   d->ready = true;
   return d;
@@ -411,7 +419,8 @@ int star_attn_rope(const star_attn_shape* shape, int32_t n_heads, int64_t n_toke
 static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t cache_len,
                        int64_t q_len, void* Qq, const void* Kq, const void* Vq, void* K_cache,
                        void* V_cache, float* O_part, float* LSE_part, void* O, bool pair, float* A,
-                       float* LSE, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                       float* LSE, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       bool static_scratch = false) {
   int rc = validate_shape(shape);
   if (rc != STAR_ATTN_OK) return rc;
   if (rope && (rc = validate_rope(shape, rope->theta, rope->pos0)) != STAR_ATTN_OK) return rc;
@@ -419,7 +428,8 @@ static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t c
   const bool append = !(pair && !Kq && !Vq);
   const int64_t total = cache_len + (append ? q_len : 0);
   if (total > shape->cache_capacity) return STAR_ATTN_ERR_CACHE_OVERFLOW;
-  if (!Qq || !K_cache || !V_cache || !workspace) return STAR_ATTN_ERR_NULL_POINTER;
+  if (static_scratch) workspace_bytes = STAR_ATTN_STATIC_SCRATCH_BYTES;
+  if (!Qq || !K_cache || !V_cache || (!workspace && !static_scratch)) return STAR_ATTN_ERR_NULL_POINTER;
   if (append && (!Kq || !Vq)) return STAR_ATTN_ERR_NULL_POINTER;
   if (pair ? (!A || !LSE) : !O) return STAR_ATTN_ERR_NULL_POINTER;
   if ((O_part == nullptr) != (LSE_part == nullptr)) return STAR_ATTN_ERR_NULL_POINTER;
@@ -434,6 +444,13 @@ static int phase2_impl(const star_attn_shape* shape, const Rope* rope, int64_t c
   Geom g = make_geom(shape);
   if ((int64_t)g.B * plan.s_total * ((q_len + 31) / 32) * g.Hq > (int64_t)0x7fffffff)
     return STAR_ATTN_ERR_INVALID_SHAPE;
+  if (static_scratch) {
+    // the current device's copy of the static array (its address was looked up
+    // once, with that device current)
+    DeviceState* ds = device_state();
+    if (!ds) return STAR_ATTN_ERR_LAUNCH_FAILED;
+    workspace = ds->scratch_ptr;
+  }
   hipStream_t st = (hipStream_t)hip_stream;
 
   // Algorithm 2: the new tokens' K/V join the cache before they attend.  The
@@ -495,6 +512,14 @@ int star_attn_phase2(const star_attn_shape* shape, int64_t cache_len, int64_t q_
                      workspace_bytes, hip_stream);
 }
 
+int star_attn_phase2_static(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
+                            const void* Qq, const void* Kq, const void* Vq, void* K_cache,
+                            void* V_cache, void* O, void* hip_stream) {
+  return phase2_impl(shape, nullptr, cache_len, q_len, const_cast<void*>(Qq), Kq, Vq, K_cache,
+                     V_cache, nullptr, nullptr, O, false, nullptr, nullptr, nullptr, 0, hip_stream,
+                     /*static_scratch=*/true);
+}
+
 int star_attn_phase2_partial(const star_attn_shape* shape, int64_t cache_len, int64_t q_len,
                              const void* Qq, const void* Kq, const void* Vq, void* K_cache,
                              void* V_cache, float* A, float* LSE, void* workspace,
@@ -552,7 +577,8 @@ const char* star_attn_status_string(int status) {
     case STAR_ATTN_ERR_UNSUPPORTED_DTYPE: return "unsupported dtype";
     case STAR_ATTN_ERR_ANCHOR_GT_BLOCK: return "anchor outside [0, block]";
     case STAR_ATTN_ERR_CACHE_OVERFLOW: return "cache capacity exceeded";
-    case STAR_ATTN_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case STAR_ATTN_ERR_WORKSPACE_TOO_SMALL:
+      return "workspace too small (star_attn_phase2_static: the call needs more than the static scratch)";
     case STAR_ATTN_ERR_LAUNCH_FAILED: return "kernel launch failed";
     case STAR_ATTN_ERR_MISALIGNED: return "pointer not sufficiently aligned";
     case STAR_ATTN_ERR_INVALID_MODE: return "unknown anchor mode";

@@ -42,7 +42,8 @@ def test_header_symbols_are_exported(lib):
                           "star_attn_status_string", "star_attn_kernel_path",
                           "star_attn_phase1_anchor", "star_attn_phase1_workspace_bytes",
                           "star_attn_phase1_rope", "star_attn_phase2_rope", "star_attn_rope",
-                          "star_attn_phase2_partial", "star_attn_merge", "star_attn_phase2_plan"}
+                          "star_attn_phase2_partial", "star_attn_merge", "star_attn_phase2_plan",
+                          "star_attn_phase2_static"}
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -175,6 +176,37 @@ def test_plan_query(lib):
     assert call(ctypes.byref(small), small.ctx_len, 0, 0, ctypes.byref(info)) == ERR["INVALID_SHAPE"]
     assert call(ctypes.byref(small), small.cache_capacity, 1, 0, ctypes.byref(info)) == ERR["CACHE_OVERFLOW"]
     assert call(ctypes.byref(small), small.ctx_len, 1, 0, None) == ERR["NULL_POINTER"]
+
+
+def test_static_scratch_entry_point_arguments(lib):
+    """star_attn_phase2_static validates like star_attn_phase2 and refuses a call
+    whose per-split pairs do not fit its static scratch."""
+    shape = good_shape()
+    L, cap = shape.ctx_len, shape.cache_capacity
+
+    def st(sh=shape, cache_len=L, q_len=1, Qq=0x1000, Kq=0x1000, Vq=0x1000, Kc=0x1000, Vc=0x1000,
+           O=0x1000):
+        return lib.star_attn_phase2_static(ctypes.byref(sh), cache_len, q_len, Qq, Kq, Vq, Kc, Vc, O,
+                                           None)
+
+    assert st(q_len=0) == ERR["INVALID_SHAPE"]
+    assert st(cache_len=cap) == ERR["CACHE_OVERFLOW"]
+    for arg in ("Qq", "Kq", "Vq", "Kc", "Vc", "O"):
+        assert st(**{arg: None}) == ERR["NULL_POINTER"]
+    assert st(O=0x1008) == ERR["MISALIGNED"]
+    assert st(sh=good_shape(head_dim=96)) == ERR["UNSUPPORTED_HEAD_DIM"]
+    m = re.search(r"#define\s+STAR_ATTN_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", open(HEADER).read())
+    assert m and int(m.group(1)) << int(m.group(2)) == binding.STATIC_SCRATCH_BYTES
+    # query encoding at the 128K shape: 38 MB of per-split pairs, more than the scratch
+    c3 = good_shape(n_q_heads=32, n_kv_heads=8, ctx_len=131072, block=16384, anchor=16384,
+                    cache_capacity=131072 + 384)
+    assert sa.phase2_plan(c3, 131072, 256).workspace_bytes > binding.STATIC_SCRATCH_BYTES
+    assert st(sh=c3, cache_len=131072, q_len=256) == ERR["WORKSPACE_TOO_SMALL"]
+    # every decode-sized call fits
+    for sh in (c3, good_shape(n_q_heads=64, n_kv_heads=8, batch=4, ctx_len=131072, block=8192,
+                              anchor=2048, cache_capacity=131072 + 192)):
+        for q in (1, 2):
+            assert sa.phase2_plan(sh, sh.ctx_len, q).workspace_bytes <= binding.STATIC_SCRATCH_BYTES
 
 
 def test_kernel_path_names(lib):
@@ -333,6 +365,7 @@ def test_header_is_plain_c(tmp_path):
         "  rc |= star_attn_phase2_partial(&s, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
         "  rc |= star_attn_merge(&s, 1, 1, 0, 0, 0, 0, 0, 0);\n"
         "  { star_attn_plan_info pi; rc |= star_attn_phase2_plan(&s, 0, 1, 0, &pi); }\n"
+        "  rc |= star_attn_phase2_static(&s, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
         "  return (rc != 0 && star_attn_workspace_bytes(&s, 1) == 0 &&\n"
         "          star_attn_phase1_workspace_bytes(&s, 0) == 0 &&\n"
         "          star_attn_status_string(rc) != 0 && star_attn_kernel_path(&s) == 0) ? 0 : 1;\n"
