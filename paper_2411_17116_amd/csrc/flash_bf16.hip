@@ -182,6 +182,7 @@ struct LaneAddr {
   unsigned dma;        // byte offset of this thread's 16-byte unit inside its key row
   int tid;
   int j4;
+  bool upper;          // wave-uniform: the second of the two wavefronts that share a SIMD
 };
 
 // Issue the DMA of one 64-key tile of K or V into an LDS tile buffer.  Thread
@@ -468,8 +469,15 @@ __device__ __forceinline__ void tile_step(WaveState& w, const LaneAddr& la, cons
     const bool anchor_tile = t + 1 < seq.n_a;
     const int mask_from = anchor_tile ? nhi : (wave_lo < nhi ? wave_lo : nhi);
     const bool need_mask = nk0 + TKEYS > mask_from;
+    // The two wavefronts of a SIMD take turns at the higher issue priority, one
+    // stage each.  With equal priorities the arbiter keeps favouring the same one,
+    // which then reaches the tile barrier some 1100 cycles before its neighbour
+    // (541 cycles of barrier wait per wavefront and tile on average); taking turns
+    // brings both there together (218 cycles).
+    if (la.upper) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
     stage<SAFE, true, true, true, KN, VC, false, true, KN + H, VC + H>(w, la, r.sA, r.sB, r.pB, r.pA,
                                                                        c, alpha, pre);
+    if (la.upper) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
     if (SAFE) rescale(w, alpha);
     if (need_mask) mask_if_needed(r.sA, nk0, nhi, wave_lo, row_lim, la.j4, anchor_tile);
     stage<SAFE, true, true, true, KN + H, VC + H, true>(w, la, r.sB, r.sA, r.pA, r.pB, c, alpha, pre);
@@ -537,6 +545,7 @@ __device__ __forceinline__ void key_loop(WaveState& w, const LaneAddr& la, const
   } else {
     tile_step<SAFE, false, K1, V0, K0, V1>(w, la, seq, t, row_lim, wave_lo, c, lds0, r);
   }
+  __builtin_amdgcn_s_setprio(0);
 }
 
 __device__ __forceinline__ void reset_state(WaveState& w) {
@@ -559,6 +568,8 @@ __device__ __forceinline__ LaneAddr lane_addr(unsigned lds0) {
   const int lane = la.tid & 63;
   const int col = lane & 15;
   la.j4 = lane >> 4;
+  // eight wavefronts on four SIMDs: wavefronts w and w + 4 share one
+  la.upper = __builtin_amdgcn_readfirstlane((la.tid >> 8) & 1) != 0;
   // K operand: in MFMA step t, lane (col, j4) reads row col, chunk 4 j4 + t (any
   // assignment of d-chunks to (t, j4) works as long as Q uses the same one; this
   // one keeps the 16-byte reads of a wavefront free of LDS bank conflicts, the
