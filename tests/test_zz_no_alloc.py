@@ -79,3 +79,55 @@ def test_static_scratch_entry_fp32_and_its_size_limit():
     rc = lib.star_attn_phase2_static(ctypes.byref(big), 131072, 256, 0x1000, 0x1000, 0x1000, 0x1000,
                                      0x1000, 0x1000, None)
     assert rc == -7                                    # STAR_ATTN_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_static_scratch_entry_under_graph_capture():
+    """The callers the entry point is for: a decode loop captured into a HIP graph
+    with no workspace to bring.  Every replay (with eager work in between) gives
+    the bits of the eager star_attn_phase2 loop."""
+    cfg = workloads.StarConfig("noalloc-graph", "bf16", 1, 8, 2, 128, 8192, 2048, 2048, 24, 5, seed=47)
+    inp, ws_run, st_run = _pair(cfg)
+    Qd = [inp.Qd[:, t:t + 1].contiguous() for t in range(cfg.nd)]
+    Kd = [inp.Kd[:, t:t + 1].contiguous() for t in range(cfg.nd)]
+    Vd = [inp.Vd[:, t:t + 1].contiguous() for t in range(cfg.nd)]
+    want = [torch.empty_like(Qd[0]) for _ in range(cfg.nd)]
+    got = [torch.empty_like(Qd[0]) for _ in range(cfg.nd)]
+    Oq_w, Oq_g = torch.empty_like(inp.Qq), torch.empty_like(inp.Qq)
+    sa.phase2(ws_run.shape, cfg.L, inp.Qq, inp.Kq, inp.Vq, ws_run.Kc, ws_run.Vc, Oq_w, ws_run.ws)
+    for t in range(cfg.nd):
+        sa.phase2(ws_run.shape, cfg.L + cfg.lq + t, Qd[t], Kd[t], Vd[t], ws_run.Kc, ws_run.Vc, want[t],
+                  ws_run.ws)
+    torch.cuda.synchronize()
+    Kc0, Vc0 = st_run.Kc.clone(), st_run.Vc.clone()
+
+    def steps():
+        sa.phase2_static(st_run.shape, cfg.L, inp.Qq, inp.Kq, inp.Vq, st_run.Kc, st_run.Vc, Oq_g)
+        for t in range(cfg.nd):
+            sa.phase2_static(st_run.shape, cfg.L + cfg.lq + t, Qd[t], Kd[t], Vd[t], st_run.Kc,
+                             st_run.Vc, got[t])
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        steps()                                   # warm-up on the capture stream (first-call look-up)
+    side.synchronize()
+    st_run.Kc.copy_(Kc0)
+    st_run.Vc.copy_(Vc0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        steps()
+    for rep in range(3):
+        print(f"replay {rep}", flush=True)
+        st_run.Kc.copy_(Kc0)
+        st_run.Vc.copy_(Vc0)
+        for o in got:
+            o.fill_(7.0)
+        Oq_g.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Oq_g, Oq_w), f"replay {rep}, query call"
+        for t in range(cfg.nd):
+            assert torch.equal(got[t], want[t]), f"replay {rep}, decode step {t}"
+        assert torch.equal(st_run.Kc, ws_run.Kc) and torch.equal(st_run.Vc, ws_run.Vc)
