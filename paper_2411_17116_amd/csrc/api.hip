@@ -36,6 +36,7 @@ struct DeviceState {
   unsigned char* scratch_ptr = nullptr;     // device address of scratch on this device
   hipEvent_t slot_done[TICKET_SLOTS] = {};  // recorded behind the launch that last used a slot
   bool slot_used[TICKET_SLOTS] = {};
+  bool slot_pending[TICKET_SLOTS] = {};     // taken by a call that has not recorded its event yet
   unsigned next_slot = 0;
 };
 static DeviceState g_dev[MAX_DEVICES];
@@ -73,6 +74,7 @@ static int acquire_ticket_slot(DeviceState* d) {
   std::lock_guard<std::mutex> lock(g_dev_mu);
   for (int k = 0; k < TICKET_SLOTS; ++k) {
     const int slot = (int)((d->next_slot + k) % TICKET_SLOTS);
+    if (d->slot_pending[slot]) continue;       // another thread is between taking it and its launch
     if (d->slot_used[slot] && hipEventQuery(d->slot_done[slot]) != hipSuccess) {
       (void)hipGetLastError();          // hipErrorNotReady is an answer, not a failure
       continue;
@@ -81,6 +83,7 @@ static int acquire_ticket_slot(DeviceState* d) {
         hipEventCreateWithFlags(&d->slot_done[slot], hipEventDisableTiming) != hipSuccess)
       return -1;
     d->slot_used[slot] = true;
+    d->slot_pending[slot] = true;
     d->next_slot = (unsigned)(slot + 1);
     return slot;
   }
@@ -327,6 +330,17 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
       tickets = ds->tickets + 8 * slot;
     }
   }
+  // On every way out: the set is free again once everything enqueued so far is
+  // done.  A set whose event could not be recorded is never handed out again.
+  struct SlotRelease {
+    DeviceState* ds; int slot; hipStream_t st;
+    ~SlotRelease() {
+      if (slot < 0) return;
+      if (hipEventRecord(ds->slot_done[slot], st) != hipSuccess) { (void)hipGetLastError(); return; }
+      std::lock_guard<std::mutex> lock(g_dev_mu);
+      ds->slot_pending[slot] = false;
+    }
+  } slot_release{ds, slot, st};
   // Algorithm 1: keep the K/V of every block once (anchor copies never exist here).
   // The bf16 attention kernel reads plain inputs where they are and files them in
   // the caches itself; rotated keys and the fp32 kernel go through the caches.
@@ -363,8 +377,6 @@ static int phase1_impl(const star_attn_shape* shape, int anchor_mode, const Rope
     a.Ka = wk; a.Va = wv;
   }
   hipError_t e = shape->dtype == STAR_ATTN_F32 ? launch_phase1_f32(a, st) : launch_phase1_bf16(a, st);
-  // the library's own counters are free again once everything enqueued so far is done
-  if (slot >= 0 && hipEventRecord(ds->slot_done[slot], st) != hipSuccess) e = hipErrorUnknown;
   return e == hipSuccess ? STAR_ATTN_OK : STAR_ATTN_ERR_LAUNCH_FAILED;
 }
 

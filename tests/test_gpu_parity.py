@@ -192,6 +192,54 @@ def test_phase1_without_workspace_never_shares_a_counter_set():
     assert all(torch.equal(r.O_ctx, ref.O_ctx) for r in runs)
 
 
+def test_phase1_static_counter_sets_taken_from_several_host_threads():
+    """Four host threads, each launching on a stream of its own without a
+    workspace (ctypes drops the interpreter lock during the call, so the calls
+    really overlap): a counter set that one thread has taken but not yet launched
+    on must not be handed to another.  Every launch that ran gives the first
+    launch's bits; the rest are refused as busy."""
+    import threading
+    cfg = workloads.StarConfig("queues_mt", "bf16", 1, 8, 2, 128, 3000, 512, 200, 1, 0, seed=17)
+    inp = workloads.make_inputs(cfg, "cuda")
+    ref = ph.HipRun(cfg, inp)
+    ref.phase1()
+    torch.cuda.synchronize()
+    n_threads = 4
+    streams = [torch.cuda.Stream() for _ in range(n_threads)]
+    runs = [[ph.HipRun(cfg, inp) for _ in range(2)] for _ in range(n_threads)]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    counts = [[0, 0] for _ in range(n_threads)]
+    errors = []
+
+    def worker(k):
+        try:
+            for i in range(40):
+                try:
+                    runs[k][i % 2].phase1(own_workspace=False, stream=streams[k])
+                    counts[k][0] += 1
+                except sa.StarAttnError as e:
+                    if e.code != -11:                      # STAR_ATTN_ERR_BUSY
+                        raise
+                    counts[k][1] += 1
+        except Exception as e:                             # noqa: BLE001 - reported below
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    print(f"\n[static counter sets, {n_threads} threads] (ran, busy) per thread: {counts}", flush=True)
+    assert not errors, errors
+    assert sum(c[0] for c in counts) >= 64
+    for k in range(n_threads):
+        for r in runs[k]:
+            assert torch.equal(r.O_ctx, ref.O_ctx) and torch.equal(r.LSE_ctx, ref.LSE_ctx)
+            assert torch.equal(r.Kc, ref.Kc) and torch.equal(r.Vc, ref.Vc)
+
+
 @pytest.mark.parametrize("Hq,Hkv,lq", [(4, 1, 4), (4, 2, 5), (8, 1, 2), (6, 2, 3), (1, 1, 16)])
 def test_decode_sized_calls_with_several_new_tokens(Hq, Hkv, lq):
     """G * q_len <= 16 rows per KV head take the streaming split-KV kernel even
