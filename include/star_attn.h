@@ -38,6 +38,10 @@
  *     refused a kernel launch) may leave earlier kernels of the call on the
  *     stream, e.g. Q already rotated in place by a *_rope entry point.
  *   - Results are deterministic (no floating-point atomics).
+ *   - Host threads: every entry point may be called from several threads at
+ *     once (the per-device set-up and the hand-out of the static counter sets
+ *     are behind a mutex); star_attn_phase2_static is the exception stated at
+ *     its declaration, because its calls share one scratch buffer per GPU.
  */
 #ifndef STAR_ATTN_H
 #define STAR_ATTN_H
